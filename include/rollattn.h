@@ -1,0 +1,154 @@
+/*
+ * librollattn -- batched attention over a paged KV cache for multi-turn rollouts,
+ * hand-written for gfx950 (MI355X).  C ABI, plain pointers and sizes only.
+ *
+ * The operation is the inference engine's per-step attention during the rollout
+ * stage: every engine step runs a decode or a prefill step for a batch of requests
+ * (Section 6.1, inference worker loop, "Step Wise Command Processing"); decode is the
+ * memory-bandwidth-bound phase and prefill the compute-bound one (Section 3.1,
+ * "Stage Computation"); with prefix caching on (Section 7.1, "Evaluation Setup") the
+ * history of a multi-turn trajectory stays cached, so a new turn only prefills the
+ * observation chunk on top of it.  The paper names these phases and their workload
+ * shape; the result itself is textbook softmax attention:
+ *
+ *   trajectory b, query head h, chunk row i of n_b (decode: n_b = 1)
+ *   g   = h / (Hq / Hkv)                         KV head of query head h
+ *   pos = L_b - n_b + i                          position of the query token; the
+ *                                                chunk's own K/V are already cached and
+ *                                                counted in L_b = ctx_lens[b]
+ *   token t in [0, pos] lives in physical page page_table[b][t / 16], slot t % 16
+ *   out = sum_t softmax_t(sm_scale * <q, k_t>) v_t ,   an all-zero row when L_b = 0
+ *
+ * Memory.  All array arguments are DEVICE pointers unless marked "host".  The caller
+ * owns every buffer; the library allocates nothing, frees nothing and keeps no state
+ * between calls apart from the optional profiling events below.  Inputs are only
+ * read; `out` and `workspace` are the only memory written.  Every device pointer must
+ * be 16-byte aligned.  Layouts are dense row-major:
+ *   q, out        [rows][Hq][D]                 rows = B (decode) or total_q (append)
+ *   k_pages,
+ *   v_pages       [num_pages][Hkv][16][D]       one page table serves both pools
+ *   page_table    [B][max_pages_per_seq] int32  entries past ceil(L_b/16)-1 are never
+ *                                               read, nor are slots >= L_b % 16 of a
+ *                                               trajectory's last page
+ *   k_scale,
+ *   v_scale       [num_pages] float             FP8 pools only: element = code * scale
+ *                                               of its physical page (per pool)
+ * Supported element types: q/out F32 with kv F32 (D = 64 or 128); q/out BF16 with kv
+ * BF16 or FP8_E4M3 (OCP E4M3, no infinities, max 448; D = 64 or 128).  Accumulation
+ * is float.  Hq / Hkv may be any positive integer (at most 256 for BF16 attn_append).
+ *
+ * Execution.  Calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*,
+ * NULL = the default stream) and return without synchronising; nothing is copied to
+ * the host.  Two calls that share a workspace must be ordered on one stream.
+ *
+ * Errors.  Every entry point returns 0 on success or a negative rollattn_status.
+ * All argument checks run on the host before anything is launched, so they behave
+ * the same without a GPU.  Contents of device arrays are not checked: a page id
+ * outside [0, num_pages) or L_b > 16 * max_pages_per_seq is undefined behaviour.
+ */
+#ifndef ROLLATTN_H
+#define ROLLATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ROLLATTN_F32 = 0,
+  ROLLATTN_BF16 = 1,
+  ROLLATTN_FP8_E4M3 = 2
+} rollattn_dtype;
+
+typedef enum {
+  ROLLATTN_OK = 0,
+  ROLLATTN_EINVAL = -1,     /* null pointer, negative size, NULL descriptor            */
+  ROLLATTN_ESHAPE = -2,     /* Hq % Hkv != 0, unsupported head_dim or page_size        */
+  ROLLATTN_EDTYPE = -3,     /* unsupported q/kv type pair, FP8 without scales          */
+  ROLLATTN_EALIGN = -4,     /* a device pointer is not 16-byte aligned                 */
+  ROLLATTN_EWORKSPACE = -5, /* workspace smaller than rollattn_workspace_bytes()       */
+  ROLLATTN_EHIP = -6        /* a HIP call failed; text via rollattn_last_hip_error()   */
+} rollattn_status;
+
+typedef struct {
+  int32_t batch;             /* B >= 0                                              */
+  int32_t num_q_heads;       /* Hq                                                  */
+  int32_t num_kv_heads;      /* Hkv, Hq % Hkv == 0                                  */
+  int32_t head_dim;          /* D, 64 or 128                                        */
+  int32_t page_size;         /* 16                                                  */
+  int32_t max_pages_per_seq; /* row stride of page_table, >= 1                      */
+  int64_t num_pages;         /* physical pool size                                  */
+  int32_t q_dtype;           /* rollattn_dtype of q and out                         */
+  int32_t kv_dtype;          /* rollattn_dtype of both pools                        */
+  float sm_scale;            /* softmax scale, e.g. 1/sqrt(D)                       */
+  const float *k_scale;      /* device [num_pages], FP8 only, else NULL             */
+  const float *v_scale;      /* device [num_pages], FP8 only, else NULL             */
+} rollattn_desc;
+
+/* Decode step: one query token per trajectory at position L_b - 1 (Section 3.1, the
+ * bandwidth-bound phase; Section 6.1, the engine's decode step).  The KV range of each
+ * trajectory is partitioned over workgroups by a plan computed on the device from
+ * ctx_lens alone (never from page ids), partial results are merged with the
+ * log-sum-exp rule, so results do not depend on where pages sit physically.
+ *   q [B][Hq][D], out [B][Hq][D], ctx_lens [B] int32 (device).
+ * B == 0 succeeds without a launch. */
+int attn_decode(const rollattn_desc *desc, const void *q, const void *k_pages, const void *v_pages,
+                const int32_t *page_table, const int32_t *ctx_lens, void *out, void *workspace,
+                size_t workspace_bytes, void *hip_stream);
+
+/* Observation-append step: trajectory b contributes n_b = q_lens[b] query rows (its new
+ * chunk, packed consecutively in q_chunk in batch order) that attend causally inside the
+ * chunk and fully to the cached prefix (Section 3.1, the compute-bound prefill phase, on
+ * top of the prefix cache of Section 7.1).  ctx_lens INCLUDES the chunk.  q_offsets is the
+ * exclusive scan of q_lens ([B+1], device); total_q = q_offsets[B] and max_q_len >=
+ * max n_b are host scalars (they size the launch).  Requires n_b <= L_b.  With every
+ * n_b == 1 the result equals attn_decode.  total_q == 0 succeeds without a launch. */
+int attn_append(const rollattn_desc *desc, const void *q_chunk, const int32_t *q_lens,
+                const int32_t *q_offsets, int32_t total_q, int32_t max_q_len, const void *k_pages,
+                const void *v_pages, const int32_t *page_table, const int32_t *ctx_lens, void *out,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of workspace either call needs for this descriptor; total_q is the number of
+ * query rows (B for decode).  Depends on the descriptor only, never on device data.
+ * Returns 0 for an invalid descriptor. */
+size_t rollattn_workspace_bytes(const rollattn_desc *desc, int32_t total_q);
+
+/* Paging logic alone (Section 7.1's prefix cache as a data structure): copies logical
+ * tokens [0, L_b) of trajectory b, KV head kv_head, unconverted, from `pages` to dst
+ * ([L_b][D] elements of kv_dtype, device), reading L_b from ctx_lens on the device. */
+int rollattn_debug_gather(const rollattn_desc *desc, const void *pages, const int32_t *page_table,
+                          const int32_t *ctx_lens, int32_t b, int32_t kv_head, void *dst,
+                          void *hip_stream);
+
+/* Host twin of the decode partition rule, for bit-exact plan tests; runs without a GPU.
+ * ctx_lens_host [B] (host).  Writes the chunk length chosen (0 = one piece per
+ * trajectory) to *chunk_out, the number of pieces to *n_items, and, when items_out is not
+ * NULL, 4 int32 per piece: (b, first token, token count, piece index within b), ordered by
+ * b then first token.  items_out must hold 4 * rollattn_plan_capacity(desc) int32. */
+int rollattn_debug_plan(const rollattn_desc *desc, const int32_t *ctx_lens_host, int32_t *chunk_out,
+                        int32_t *items_out, int32_t *n_items);
+int32_t rollattn_plan_capacity(const rollattn_desc *desc);
+
+/* Copies the plan the last attn_decode call left in `workspace` back to the host in the
+ * format of rollattn_debug_plan (synchronises the stream).  ctx_lens is the same device
+ * array that call was given. */
+int rollattn_debug_read_plan(const rollattn_desc *desc, const void *workspace, const int32_t *ctx_lens,
+                             int32_t *chunk_out, int32_t *items_out, int32_t *n_items, void *hip_stream);
+
+/* Optional per-kernel timing.  While enabled, attn_decode / attn_append bracket their
+ * main kernel (not the planning or merge kernels) with HIP events on the call's stream;
+ * rollattn_profile_read synchronises those events and returns up to `cap` durations in
+ * milliseconds, oldest first, then forgets them.  At most 1024 launches are kept. */
+int rollattn_profile_enable(int on);
+int rollattn_profile_read(float *ms_out, int cap);
+
+const char *rollattn_status_string(int status);
+const char *rollattn_last_hip_error(void);
+int rollattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROLLATTN_H */

@@ -1,0 +1,223 @@
+"""ctypes binding of librollattn's C ABI for torch tensors.
+
+Argument marshalling only: every step of the attention path (planning, paged loads,
+softmax, the split-K merge) runs in the library's HIP kernels.  torch supplies device
+memory and the current stream.  There is no fallback: if the shared library has not been
+built, `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librollattn.so")
+
+F32, BF16, FP8_E4M3 = 0, 1, 2
+EXPORTS = (
+    "attn_decode", "attn_append", "rollattn_workspace_bytes", "rollattn_debug_gather",
+    "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_debug_read_plan",
+    "rollattn_profile_enable", "rollattn_profile_read", "rollattn_status_string",
+    "rollattn_last_hip_error", "rollattn_version",
+)
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32),
+        ("num_pages", ctypes.c_int64), ("q_dtype", ctypes.c_int32), ("kv_dtype", ctypes.c_int32),
+        ("sm_scale", ctypes.c_float), ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
+    ]
+
+
+class RollattnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        l = lib()
+        msg = l.rollattn_status_string(status).decode()
+        if status == -6:
+            msg += ": " + l.rollattn_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_22560_amd.build` "
+                               "(or __graft_entry__.build())")
+        l = ctypes.CDLL(LIB_PATH)
+        vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
+        dp = ctypes.POINTER(Desc)
+        l.attn_decode.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        l.attn_decode.restype = ctypes.c_int
+        l.attn_append.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        l.attn_append.restype = ctypes.c_int
+        l.rollattn_workspace_bytes.argtypes = [dp, i32]
+        l.rollattn_workspace_bytes.restype = ctypes.c_size_t
+        l.rollattn_debug_gather.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp]
+        l.rollattn_debug_gather.restype = ctypes.c_int
+        l.rollattn_debug_plan.argtypes = [dp, i32p, i32p, i32p, i32p]
+        l.rollattn_debug_plan.restype = ctypes.c_int
+        l.rollattn_plan_capacity.argtypes = [dp]
+        l.rollattn_plan_capacity.restype = ctypes.c_int32
+        l.rollattn_debug_read_plan.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp]
+        l.rollattn_debug_read_plan.restype = ctypes.c_int
+        l.rollattn_profile_enable.argtypes = [ctypes.c_int]
+        l.rollattn_profile_enable.restype = ctypes.c_int
+        l.rollattn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+        l.rollattn_profile_read.restype = ctypes.c_int
+        l.rollattn_status_string.argtypes = [ctypes.c_int]
+        l.rollattn_status_string.restype = ctypes.c_char_p
+        l.rollattn_last_hip_error.argtypes = []
+        l.rollattn_last_hip_error.restype = ctypes.c_char_p
+        l.rollattn_version.argtypes = []
+        l.rollattn_version.restype = ctypes.c_int
+        _lib = l
+    return _lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype in (torch.uint8, torch.float8_e4m3fn):
+        return FP8_E4M3
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def make_desc(q, k_pages, page_table, *, sm_scale, k_scale=None, v_scale=None, batch=None) -> Desc:
+    num_pages, hkv, page_size, d = k_pages.shape
+    return Desc(
+        batch=int(page_table.shape[0] if batch is None else batch), num_q_heads=int(q.shape[1]),
+        num_kv_heads=int(hkv), head_dim=int(d), page_size=int(page_size),
+        max_pages_per_seq=int(page_table.shape[1]), num_pages=int(num_pages), q_dtype=_dtype_code(q),
+        kv_dtype=_dtype_code(k_pages), sm_scale=float(sm_scale),
+        k_scale=None if k_scale is None else k_scale.data_ptr(),
+        v_scale=None if v_scale is None else v_scale.data_ptr(),
+    )
+
+
+def workspace_bytes(desc: Desc, total_q: int) -> int:
+    return int(lib().rollattn_workspace_bytes(ctypes.byref(desc), int(total_q)))
+
+
+def alloc_workspace(desc: Desc, total_q: int, device) -> torch.Tensor:
+    n = workspace_bytes(desc, total_q)
+    if n == 0:
+        raise RollattnError(-2, "rollattn_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _check_contig(*ts):
+    for t in ts:
+        if t is not None and not t.is_contiguous():
+            raise ValueError("librollattn takes dense row-major arrays")
+
+
+def attn_decode(q, k_pages, v_pages, page_table, ctx_lens, *, sm_scale, k_scale=None, v_scale=None,
+                out=None, workspace=None, stream=None) -> torch.Tensor:
+    """out[b, h, :] = attention of q[b, h, :] over trajectory b's cached tokens."""
+    _check_contig(q, k_pages, v_pages, page_table, ctx_lens, k_scale, v_scale, out)
+    desc = make_desc(q, k_pages, page_table, sm_scale=sm_scale, k_scale=k_scale, v_scale=v_scale)
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        workspace = alloc_workspace(desc, q.shape[0], q.device)
+    rc = lib().attn_decode(ctypes.byref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(page_table),
+                           _ptr(ctx_lens), _ptr(out), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "attn_decode")
+    return out
+
+
+def attn_append(q_chunk, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, *, sm_scale, max_q_len,
+                k_scale=None, v_scale=None, out=None, workspace=None, stream=None) -> torch.Tensor:
+    """Rows of q_chunk (packed by trajectory) attend causally inside their chunk and fully to the prefix."""
+    _check_contig(q_chunk, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, k_scale, v_scale, out)
+    desc = make_desc(q_chunk, k_pages, page_table, sm_scale=sm_scale, k_scale=k_scale, v_scale=v_scale)
+    total_q = int(q_chunk.shape[0])
+    if out is None:
+        out = torch.empty_like(q_chunk)
+    if workspace is None:
+        workspace = alloc_workspace(desc, total_q, q_chunk.device)
+    rc = lib().attn_append(ctypes.byref(desc), _ptr(q_chunk), _ptr(q_lens), _ptr(q_offsets), total_q,
+                           int(max_q_len), _ptr(k_pages), _ptr(v_pages), _ptr(page_table), _ptr(ctx_lens),
+                           _ptr(out), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "attn_append")
+    return out
+
+
+def debug_gather(pages, page_table, ctx_lens, b, kv_head, length, stream=None) -> torch.Tensor:
+    """Logical tokens [0, length) of (trajectory b, KV head) copied out of a pool, unconverted."""
+    kv = _dtype_code(pages)
+    desc = Desc(batch=int(page_table.shape[0]), num_q_heads=int(pages.shape[1]), num_kv_heads=int(pages.shape[1]),
+                head_dim=int(pages.shape[3]), page_size=int(pages.shape[2]), max_pages_per_seq=int(page_table.shape[1]),
+                num_pages=int(pages.shape[0]), q_dtype=F32 if kv == F32 else BF16, kv_dtype=kv, sm_scale=1.0,
+                k_scale=None, v_scale=None)
+    dst = torch.empty((int(length), pages.shape[3]), dtype=pages.dtype, device=pages.device)
+    rc = lib().rollattn_debug_gather(ctypes.byref(desc), _ptr(pages), _ptr(page_table), _ptr(ctx_lens), int(b),
+                                     int(kv_head), _ptr(dst), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "rollattn_debug_gather")
+    return dst
+
+
+def debug_plan(desc: Desc, ctx_lens_host: np.ndarray):
+    """Host twin of the decode partition: (chunk, items [n, 4] int32)."""
+    l = lib()
+    cap = int(l.rollattn_plan_capacity(ctypes.byref(desc)))
+    lens = np.ascontiguousarray(ctx_lens_host, dtype=np.int32)
+    items = np.zeros((max(cap, 1), 4), dtype=np.int32)
+    chunk, n = ctypes.c_int32(0), ctypes.c_int32(0)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    rc = l.rollattn_debug_plan(ctypes.byref(desc), lens.ctypes.data_as(i32p), ctypes.byref(chunk),
+                               items.ctypes.data_as(i32p), ctypes.byref(n))
+    if rc:
+        raise RollattnError(rc, "rollattn_debug_plan")
+    return int(chunk.value), items[: n.value].copy()
+
+
+def read_plan(desc: Desc, workspace: torch.Tensor, ctx_lens: torch.Tensor, stream=None):
+    """The plan the last attn_decode call left in `workspace`: (chunk, items [n, 4] int32)."""
+    l = lib()
+    cap = int(l.rollattn_plan_capacity(ctypes.byref(desc)))
+    items = np.zeros((max(cap, 1), 4), dtype=np.int32)
+    chunk, n = ctypes.c_int32(0), ctypes.c_int32(0)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    rc = l.rollattn_debug_read_plan(ctypes.byref(desc), _ptr(workspace), _ptr(ctx_lens), ctypes.byref(chunk),
+                                    items.ctypes.data_as(i32p), ctypes.byref(n), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "rollattn_debug_read_plan")
+    return int(chunk.value), items[: n.value].copy()
+
+
+def profile_enable(on: bool) -> None:
+    lib().rollattn_profile_enable(1 if on else 0)
+
+
+def profile_read(cap: int = 1024) -> np.ndarray:
+    buf = (ctypes.c_float * cap)()
+    n = lib().rollattn_profile_read(buf, cap)
+    return np.frombuffer(buf, dtype=np.float32, count=n).copy()

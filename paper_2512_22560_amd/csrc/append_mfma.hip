@@ -1,0 +1,325 @@
+// Observation-append attention (chunked causal prefill on a cached prefix) for bf16 queries
+// over bf16 or FP8-E4M3 paged KV, on the gfx950 matrix cores.
+//
+// One workgroup = 256 query rows of one (trajectory, KV head): a row is a (chunk token, query
+// head of the group) pair, token-major, so the G heads that share the KV head reuse every K/V
+// tile.  Eight waves of 32 rows each walk the visible KV range in 64-token blocks (four
+// pages) that the workgroup stages once through LDS (double buffered, global loads for the
+// next block in flight while the current one is consumed).  FP8 pools are widened to bf16
+// while staging, so the tiles in LDS always hold bf16; page scales are applied in float to
+// S (K scale) and to P (V scale).  Per 32-token sub-block a wave computes
+//   S^T = K Q^T        tokens x rows, v_mfma_f32_32x32x16_bf16, K rows as A operand
+//   O^T += V^T P^T     dims x rows, V read transposed with ds_read_b64_tr_b16
+// The transposed products keep "row" on the lane axis in both accumulators: the softmax
+// state is one scalar per lane (shared by two lanes) and P goes from accumulator registers
+// straight into the B operand of the second product.
+#include "rollattn_internal.h"
+
+namespace rollattn {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kRowsPerWave = 32;
+constexpr int kTileRows = kWaves * kRowsPerWave;   // 256
+constexpr int kBlockTokens = 64;                   // KV tokens staged per step
+
+// Row t of an S^T tile holds this token of its 16-token group: the middle two quads are
+// swapped so that the 8 scores a lane ends up with are 8 consecutive tokens.
+__device__ __forceinline__ int tau(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+__device__ __forceinline__ float xor32_max(float x) {
+  uintx2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xor32_add(float x) {
+  uintx2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ void fp8x16_to_bf16(const uint4 raw, uint4& lo, uint4& hi) {
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+  uint32_t o[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    floatx2 a = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], false);
+    floatx2 b = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], true);
+    bf16x2 pa, pb;
+    pa[0] = (__bf16)a[0]; pa[1] = (__bf16)a[1];
+    pb[0] = (__bf16)b[0]; pb[1] = (__bf16)b[1];
+    o[2 * i] = __builtin_bit_cast(uint32_t, pa);
+    o[2 * i + 1] = __builtin_bit_cast(uint32_t, pb);
+  }
+  lo = make_uint4(o[0], o[1], o[2], o[3]);
+  hi = make_uint4(o[4], o[5], o[6], o[7]);
+}
+
+template <int D, bool FP8>
+__global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs a) {
+  constexpr int kRowBytes = D * 2;                 // bf16 rows in LDS
+  constexpr int kChunks = kRowBytes / 16;          // 16-byte chunks per LDS row
+  constexpr int kTileBytes = kBlockTokens * kRowBytes;
+  constexpr int kSrcRowBytes = D * (FP8 ? 1 : 2);  // row bytes in HBM
+  constexpr int kSrcChunks = kSrcRowBytes / 16;
+  constexpr int kLoads = (kBlockTokens * kSrcChunks + kThreads - 1) / kThreads;   // per pool, per thread
+  constexpr int kKK = D / 16;                      // 16-deep steps of the QK product
+  constexpr int kDT = D / 32;                      // 32-wide output tiles along D
+  static_assert((kBlockTokens * kSrcChunks) % kThreads == 0 || kBlockTokens * kSrcChunks < kThreads, "staging shape");
+
+  __shared__ __attribute__((aligned(16))) unsigned char k_lds[2][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char v_lds[2][kTileBytes];
+  __shared__ float kscale_s[2][kBlockTokens / kPageSize];
+  __shared__ float vscale_s[2][kBlockTokens / kPageSize];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n32 = lane & 31;   // row (B column) / K token row (A row) carried by this lane
+  const int h2 = lane >> 5;    // half of the contraction this lane feeds
+
+  const int group = a.group;
+  const int hkv = a.hkv;
+  const int tile_tokens = a.tile_tokens;
+  const int n_tiles = a.header[kPlanTiles];
+  const int tile = blockIdx.x / hkv;
+  const int g = blockIdx.x - tile * hkv;
+  if (tile >= n_tiles) return;
+  const int b = a.tile_b[tile];
+  const int q0 = a.tile_q0[tile];
+  const int n_b = a.q_lens[b];
+  const int ctx = a.ctx_lens[b];
+  const int tokens_here = min(tile_tokens, n_b - q0);
+  const int rows_here = tokens_here * group;
+  const int pos0 = ctx - n_b + q0;                       // position of the tile's first token
+  const int kv_end = pos0 + tokens_here;                 // tokens [0, kv_end) are visible to some row
+  const int n_blocks = (kv_end + kBlockTokens - 1) / kBlockTokens;
+  const int32_t* table = a.page_table + (size_t)b * a.max_pages;
+  const size_t tile_stride = (size_t)kPageSize * kSrcRowBytes;
+
+  // ---- this lane's query row
+  const int row = wave * kRowsPerWave + n32;
+  const bool row_ok = row < rows_here;
+  const int tok_in_tile = row / group;
+  const int head = g * group + (row - tok_in_tile * group);
+  const int my_pos = row_ok ? pos0 + tok_in_tile : -1;   // last visible token of this row
+  // wave-uniform bounds for skipping fully masked sub-blocks
+  const int wave_last_row = min(wave * kRowsPerWave + kRowsPerWave - 1, rows_here - 1);
+  const int wave_max_pos = (wave * kRowsPerWave < rows_here) ? pos0 + wave_last_row / group : -1;
+  const int wave_min_pos = pos0 + (wave * kRowsPerWave) / group;
+
+  bf16x8 qop[kKK];
+  {
+    const __bf16* qrow = (const __bf16*)a.q + ((size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head) * D;
+#pragma unroll
+    for (int kk = 0; kk < kKK; ++kk) {
+      bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (row_ok) v = *(const bf16x8*)(qrow + kk * 16 + h2 * 8);
+      qop[kk] = v;
+    }
+  }
+
+  floatx16 acc[kDT];
+#pragma unroll
+  for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  // ---- staging: thread's share of a 64-token block
+  uint4 kreg[kLoads], vreg[kLoads];
+  auto issue = [&](int blk) {
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      const int idx = j * kThreads + tid;               // 16-byte chunk index within the block
+      const int trow = idx / kSrcChunks;                // token row within the block
+      const int c = idx % kSrcChunks;
+      const int tok = blk * kBlockTokens + trow;
+      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+      if (trow < kBlockTokens && tok < ctx) {
+        const int pid = table[tok / kPageSize];
+        const size_t off = ((size_t)pid * hkv + g) * tile_stride + (size_t)(tok % kPageSize) * kSrcRowBytes + c * 16;
+        kv = *(const uint4*)((const unsigned char*)a.k_pages + off);
+        vv = *(const uint4*)((const unsigned char*)a.v_pages + off);
+      }
+      kreg[j] = kv;
+      vreg[j] = vv;
+    }
+  };
+  auto commit = [&](int blk, int buf) {
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      const int idx = j * kThreads + tid;
+      const int trow = idx / kSrcChunks;
+      const int c = idx % kSrcChunks;
+      if (trow < kBlockTokens) {
+        unsigned char* krow = k_lds[buf] + trow * kRowBytes;
+        unsigned char* vrow = v_lds[buf] + trow * kRowBytes;
+        const int kkey = trow & 15;
+        const int vkey = (trow & 7) << 1;
+        if (FP8) {
+          uint4 lo, hi;
+          fp8x16_to_bf16(kreg[j], lo, hi);
+          *(uint4*)(krow + (((2 * c) ^ kkey) & (kChunks - 1)) * 16) = lo;
+          *(uint4*)(krow + (((2 * c + 1) ^ kkey) & (kChunks - 1)) * 16) = hi;
+          fp8x16_to_bf16(vreg[j], lo, hi);
+          *(uint4*)(vrow + (((2 * c) ^ vkey) & (kChunks - 1)) * 16) = lo;
+          *(uint4*)(vrow + (((2 * c + 1) ^ vkey) & (kChunks - 1)) * 16) = hi;
+        } else {
+          *(uint4*)(krow + ((c ^ kkey) & (kChunks - 1)) * 16) = kreg[j];
+          *(uint4*)(vrow + ((c ^ vkey) & (kChunks - 1)) * 16) = vreg[j];
+        }
+      }
+    }
+    if (FP8 && tid < kBlockTokens / kPageSize) {
+      const int tok = blk * kBlockTokens + tid * kPageSize;
+      float ks = 1.f, vs = 1.f;
+      if (tok < ctx) {
+        const int pid = table[tok / kPageSize];
+        ks = a.k_scale[pid];
+        vs = a.v_scale[pid];
+      }
+      kscale_s[buf][tid] = ks;
+      vscale_s[buf][tid] = vs;
+    }
+  };
+
+  auto compute = [&](int blk, int buf) {
+#pragma unroll
+    for (int sub = 0; sub < kBlockTokens / 32; ++sub) {
+      const int tok0 = blk * kBlockTokens + sub * 32;
+      if (tok0 > wave_max_pos) continue;                 // nothing visible to this wave (uniform)
+      // ---- S^T (32 tokens x 32 rows)
+      floatx16 s;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+      {
+        const int t = sub * 32 + (n32 & 16) + tau(n32 & 15);
+        const unsigned char* rowp = k_lds[buf] + t * kRowBytes;
+        const int key = t & 15;
+#pragma unroll
+        for (int kk = 0; kk < kKK; ++kk) {
+          const int c = ((kk * 2 + h2) ^ key) & (kChunks - 1);
+          const bf16x8 kop = *(const bf16x8*)(rowp + c * 16);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qop[kk], s, 0, 0, 0);
+        }
+      }
+      // register i of this lane is token tok0 + (i/8)*16 + h2*8 + (i%8) of row n32
+      float x[16];
+      const bool need_mask = tok0 + 31 > wave_min_pos;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float sc = a.scale_log2;
+        if (FP8) sc *= kscale_s[buf][sub * 2 + (i >> 3)];
+        x[i] = s[i] * sc;
+      }
+      if (need_mask) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int tok = tok0 + (i >> 3) * 16 + h2 * 8 + (i & 7);
+          if (tok > my_pos) x[i] = -INFINITY;
+        }
+      }
+      float mx = x[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
+      mx = xor32_max(mx);
+      const float m_new = fmaxf(m_run, mx);
+      // rows that see nothing yet (padding rows, or causal rows ahead of this block) keep -inf
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+      float psum = 0.f;
+      bf16x8 pop[2];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float p = __builtin_amdgcn_exp2f(x[i] - m_safe);
+        psum += p;
+        pop[i >> 3][i & 7] = (__bf16)(FP8 ? p * vscale_s[buf][sub * 2 + (i >> 3)] : p);
+      }
+      l_run = l_run * alpha + psum;
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run)) {
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
+      }
+      m_run = m_new;
+      // ---- O^T += V^T P^T
+      typedef __attribute__((address_space(3))) shortx4 lds_s4;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt) {
+          bf16x8 vop;
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf) {
+            const int j = lane & 15;
+            const int t = sub * 32 + ks * 16 + h2 * 8 + hf * 4 + (j >> 2);
+            const int c = ((dt * 4 + ((lane >> 4) & 1) * 2 + ((j & 3) >> 1)) ^ ((t & 7) << 1)) & (kChunks - 1);
+            const shortx4 raw = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (lds_s4*)(v_lds[buf] + t * kRowBytes + c * 16 + (j & 1) * 8));
+            const bf16x4 h4 = __builtin_bit_cast(bf16x4, raw);
+            vop[hf * 4 + 0] = h4[0]; vop[hf * 4 + 1] = h4[1]; vop[hf * 4 + 2] = h4[2]; vop[hf * 4 + 3] = h4[3];
+          }
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], acc[dt], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  // ---- main loop
+  issue(0);
+  commit(0, 0);
+  __syncthreads();
+  for (int blk = 0; blk < n_blocks; ++blk) {
+    const int buf = blk & 1;
+    if (blk + 1 < n_blocks) issue(blk + 1);
+    compute(blk, buf);
+    if (blk + 1 < n_blocks) commit(blk + 1, buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- normalise and store: lane (row n32, half h2) owns dims dt*32 + (i/4)*8 + h2*4 + i%4
+  l_run = xor32_add(l_run);
+  if (row_ok) {
+    const float inv = 1.f / l_run;
+    __bf16* orow = (__bf16*)a.out + ((size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head) * D;
+#pragma unroll
+    for (int dt = 0; dt < kDT; ++dt) {
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        bf16x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(acc[dt][i4 * 4 + e] * inv);
+        *(bf16x4*)(orow + dt * 32 + i4 * 8 + h2 * 4) = pk;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_append_mfma(const AppendArgs& a, int head_dim, bool fp8, int grid, hipStream_t s) {
+  if (head_dim == 128 && !fp8) {
+    hipLaunchKernelGGL((append_mfma_kernel<128, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 128 && fp8) {
+    hipLaunchKernelGGL((append_mfma_kernel<128, true>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 64 && !fp8) {
+    hipLaunchKernelGGL((append_mfma_kernel<64, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 64 && fp8) {
+    hipLaunchKernelGGL((append_mfma_kernel<64, true>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace rollattn

@@ -1,0 +1,112 @@
+// Split-K merge: one wave per (trajectory, query head) folds the per-piece partial results
+// (max m_s in log2 units, sum l_s, un-normalised o_s) into the final row:
+//   M = max_s m_s ;  out = sum_s 2^(m_s - M) o_s / sum_s 2^(m_s - M) l_s
+// which equals the softmax over the whole context.  Rows with a single piece were already
+// written by the main kernel; rows with no piece (empty context) are zero-filled here.
+#include "rollattn_internal.h"
+
+namespace rollattn {
+
+namespace {
+
+constexpr int kThreads = 256;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+template <int D, bool OUT_BF16>
+__global__ __launch_bounds__(kThreads) void combine_kernel(const DecodeArgs a) {
+  constexpr int kPer = D / 64;   // consecutive output elements per lane
+  const int lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);   // b * Hq + h
+  if (row >= (long)a.batch * a.hq) return;
+  const int b = (int)(row / a.hq);
+  const int h = (int)(row % a.hq);
+  const int first = a.row_first[b];
+  const int n = a.row_first[b + 1] - first;
+  if (n == 1) return;
+  float o[kPer];
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) o[e] = 0.f;
+  float inv = 0.f;
+  if (n > 1) {
+    const int g = h / a.group, j = h % a.group;
+    float mmax = -INFINITY;
+    for (int s = lane; s < n; s += 64) {
+      const size_t slot = (size_t)(first + s) * a.hkv + g;
+      mmax = fmaxf(mmax, a.partial_ml[(slot * a.group + j) * 2]);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, off, 64));
+    float lsum = 0.f;
+    for (int s = 0; s < n; ++s) {
+      const size_t slot = (size_t)(first + s) * a.hkv + g;
+      const float* ml = a.partial_ml + (slot * a.group + j) * 2;
+      const float f = __builtin_amdgcn_exp2f(ml[0] - mmax);
+      lsum += f * ml[1];
+      const float* src = a.partial_o + (slot * a.group + j) * D + lane * kPer;
+#pragma unroll
+      for (int e = 0; e < kPer; ++e) o[e] += f * src[e];
+    }
+    inv = 1.f / lsum;
+  }
+  if (OUT_BF16) {
+    __bf16* dst = (__bf16*)a.out + (size_t)row * D + lane * kPer;
+    if (kPer == 2) {
+      bf16x2 pr;
+      pr[0] = (__bf16)(o[0] * inv);
+      pr[1] = (__bf16)(o[kPer - 1] * inv);
+      *(bf16x2*)dst = pr;
+    } else {
+      dst[0] = (__bf16)(o[0] * inv);
+    }
+  } else {
+    float* dst = (float*)a.out + (size_t)row * D + lane * kPer;
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) dst[e] = o[e] * inv;
+  }
+}
+
+// Copies logical tokens of one (trajectory, KV head) out of a pool, byte for byte.
+__global__ __launch_bounds__(kThreads) void gather_kernel(const unsigned char* pages, const int32_t* page_table,
+                                                          const int32_t* ctx_lens, int32_t b, int32_t kv_head,
+                                                          int32_t hkv, int32_t max_pages, int32_t row_bytes,
+                                                          unsigned char* dst) {
+  const int len = ctx_lens[b];
+  const int vec_per_row = row_bytes / 16;
+  const long n_vec = (long)len * vec_per_row;
+  for (long i = (long)blockIdx.x * kThreads + threadIdx.x; i < n_vec; i += (long)gridDim.x * kThreads) {
+    const int t = (int)(i / vec_per_row), c = (int)(i % vec_per_row);
+    const int pid = page_table[(size_t)b * max_pages + t / kPageSize];
+    const size_t off = (((size_t)pid * hkv + kv_head) * kPageSize + (t % kPageSize)) * row_bytes + c * 16;
+    *(uint4*)(dst + (size_t)t * row_bytes + c * 16) = *(const uint4*)(pages + off);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_combine(const DecodeArgs& a, int head_dim, bool out_bf16, hipStream_t s) {
+  const long rows = (long)a.batch * a.hq;
+  const int grid = (int)((rows + kThreads / 64 - 1) / (kThreads / 64));
+  if (grid == 0) return hipSuccess;
+  if (head_dim == 128 && out_bf16) {
+    hipLaunchKernelGGL((combine_kernel<128, true>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 128) {
+    hipLaunchKernelGGL((combine_kernel<128, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 64 && out_bf16) {
+    hipLaunchKernelGGL((combine_kernel<64, true>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 64) {
+    hipLaunchKernelGGL((combine_kernel<64, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gather(const void* pages, const int32_t* page_table, const int32_t* ctx_lens, int32_t b,
+                         int32_t kv_head, int32_t hkv, int32_t max_pages, int32_t row_bytes, void* dst,
+                         hipStream_t s) {
+  hipLaunchKernelGGL(gather_kernel, dim3(64), dim3(kThreads), 0, s, (const unsigned char*)pages, page_table,
+                     ctx_lens, b, kv_head, hkv, max_pages, row_bytes, (unsigned char*)dst);
+  return hipGetLastError();
+}
+
+}  // namespace rollattn

@@ -7,8 +7,8 @@ HIP binding nor the CPU oracle; tests and the benchmark hand its output to both.
 Shapes follow the workload the paper describes for agentic rollouts: contexts up to
 32k tokens in the evaluation and tens of thousands in production, long-tailed
 lengths whose maximum is several times the mean, a batch of 512 trajectories, and
-turns that append an observation chunk to a cached history (Section 8.1 "Evaluation
-Setup", Section 9 production statistics, Section 2.1 on multi-turn trajectories).
+turns that append an observation chunk to a cached history (Section 7.1 "Evaluation
+Setup", Section 8 production statistics, Section 2.1 on multi-turn trajectories).
 Values are i.i.d. N(0,1): attention cost depends on shapes and lengths only.
 
 Recipe (all integers from numpy's PCG64 `default_rng(seed)`, drawn in this order:

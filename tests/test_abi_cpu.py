@@ -1,0 +1,86 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, rejects bad arguments before touching the device, and its host twin of the
+decode partition rule agrees integer for integer with the oracle's statement of the rule."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import attention as O
+from paper_2512_22560_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _desc(**kw):
+    base = dict(batch=4, num_q_heads=8, num_kv_heads=2, head_dim=64, page_size=16, max_pages_per_seq=16,
+                num_pages=43, q_dtype=B.F32, kv_dtype=B.F32, sm_scale=0.125, k_scale=None, v_scale=None)
+    base.update(kw)
+    return B.Desc(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "rollattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(attn_\w+|rollattn_\w+)\s*\(", text))
+    declared -= {"rollattn_desc", "rollattn_status", "rollattn_dtype"}
+    assert declared == set(B.EXPORTS)
+    lib = B.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.rollattn_version() >= 100
+
+
+def test_descriptor_errors_are_reported_before_any_launch():
+    lib = B.lib()
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    def decode(d, q=fake, ws=fake, ws_bytes=1 << 40):
+        return lib.attn_decode(ctypes.byref(d), q, fake, fake, fake, fake, fake, ws, ws_bytes, None)
+    assert decode(_desc(num_q_heads=7)) == -2                      # Hq % Hkv
+    assert decode(_desc(head_dim=96)) == -2
+    assert decode(_desc(page_size=32)) == -2
+    assert decode(_desc(q_dtype=B.F32, kv_dtype=B.BF16)) == -3
+    assert decode(_desc(q_dtype=B.BF16, kv_dtype=B.FP8_E4M3, head_dim=128)) == -3   # no scales
+    assert decode(_desc(batch=-1)) == -1
+    assert decode(_desc(), q=None) == -1
+    assert decode(_desc(), q=ctypes.c_void_p(0x1008)) == -4
+    assert decode(_desc(), ws_bytes=16) == -5
+    assert decode(_desc(batch=0)) == 0                             # empty batch: success, no launch
+    assert lib.attn_decode(None, fake, fake, fake, fake, fake, fake, fake, 0, None) == -1
+    assert lib.attn_append(ctypes.byref(_desc()), fake, fake, fake, 0, 0, fake, fake, fake, fake, fake, fake, 0, None) == 0
+    assert lib.attn_append(ctypes.byref(_desc()), fake, fake, fake, -1, 0, fake, fake, fake, fake, fake, fake, 0, None) == -1
+    assert lib.attn_append(ctypes.byref(_desc()), fake, fake, fake, 8, 2, fake, fake, fake, fake, fake, fake, 16, None) == -5
+    for code in range(-6, 1):
+        assert lib.rollattn_status_string(code)
+    assert lib.rollattn_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 4) == 0
+    assert lib.rollattn_workspace_bytes(ctypes.byref(_desc()), 4) > 0
+    assert lib.rollattn_profile_read(None, 0) == 0
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_host_plan_twin_matches_the_oracle_rule(seed):
+    rng = np.random.default_rng(seed)
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    batch = int(rng.choice([1, 3, 64, 700, 5000]))
+    hi = int(rng.choice([40, 3000, 70000]))
+    lens = rng.integers(0, hi, batch).astype(np.int32)
+    d = _desc(batch=batch, num_kv_heads=hkv, num_q_heads=hkv * 4, max_pages_per_seq=hi // 16 + 1)
+    chunk, items = B.debug_plan(d, lens)
+    ref_chunk, ref_items, _ = O.split_plan(lens, hkv)
+    assert chunk == ref_chunk
+    assert np.array_equal(items, ref_items)
+
+
+def test_plan_on_the_benchmark_length_draws():
+    from paper_2512_22560_amd import workloads as W
+    for c in (2, 3):
+        w = W.CONFIGS[c]
+        lens, _, table, npages = W.draw_structure(w)
+        d = _desc(batch=w.batch, num_kv_heads=w.num_kv_heads, num_q_heads=w.num_q_heads, head_dim=128,
+                  max_pages_per_seq=table.shape[1], num_pages=npages, q_dtype=B.BF16, kv_dtype=B.BF16)
+        chunk, items = B.debug_plan(d, lens)
+        ref_chunk, ref_items, _ = O.split_plan(lens, w.num_kv_heads)
+        assert chunk == ref_chunk and np.array_equal(items, ref_items)
+        assert items[:, 2].sum() == lens.sum()

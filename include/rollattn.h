@@ -89,9 +89,10 @@ typedef struct {
 
 /* Decode step: one query token per trajectory at position L_b - 1 (Section 3.1, the
  * bandwidth-bound phase; Section 6.1, the engine's decode step).  The KV range of each
- * trajectory is partitioned over workgroups by a plan computed on the device from
- * ctx_lens alone (never from page ids), partial results are merged with the
- * log-sum-exp rule, so results do not depend on where pages sit physically.
+ * trajectory is partitioned over wavefronts by a plan computed on the device from
+ * ctx_lens alone (never from page ids) and partial results are merged with the
+ * log-sum-exp rule in a fixed order, so results are reproducible bit for bit and do not
+ * depend on where pages sit physically.
  *   q [B][Hq][D], out [B][Hq][D], ctx_lens [B] int32 (device).
  * B == 0 succeeds without a launch. */
 int attn_decode(const rollattn_desc *desc, const void *q, const void *k_pages, const void *v_pages,
@@ -123,19 +124,28 @@ int rollattn_debug_gather(const rollattn_desc *desc, const void *pages, const in
                           void *hip_stream);
 
 /* Host twin of the decode partition rule, for bit-exact plan tests; runs without a GPU.
- * ctx_lens_host [B] (host).  Writes the chunk length chosen (0 = one piece per
- * trajectory) to *chunk_out, the number of pieces to *n_items, and, when items_out is not
- * NULL, 4 int32 per piece: (b, first token, token count, piece index within b), ordered by
- * b then first token.  items_out must hold 4 * rollattn_plan_capacity(desc) int32. */
-int rollattn_debug_plan(const rollattn_desc *desc, const int32_t *ctx_lens_host, int32_t *chunk_out,
-                        int32_t *items_out, int32_t *n_items);
+ * The rule: each trajectory is cut into blocks of 32 tokens; a "row" is (trajectory b, r) with
+ * r = kv_head * tiles + head_tile enumerating KV heads and, when the group is larger than one
+ * tile (16 query heads for BF16, 4 for F32), the tiles of the group; rows are laid end to end,
+ * b outermost, each with ceil(L_b / 32) blocks; the sequence of T blocks is dealt to the W =
+ * rollattn_plan_workers() workers in equal contiguous runs of per = max(1, ceil(T / W)) blocks.
+ * ctx_lens_host [B] (host).  Writes per and T, the number of row segments the workers walk to
+ * *n_segments and, when segments_out is not NULL, 6 int32 per segment in worker order:
+ * (worker, b, r, first block, block count, slot) with slot = -1 when the segment is the whole
+ * row (the worker writes the output itself), else the partial slot (0: first segment of the
+ * worker's run, 1: its last) handed to the merge.  segments_out must hold
+ * 6 * rollattn_plan_capacity(desc) int32. */
+int rollattn_debug_plan(const rollattn_desc *desc, const int32_t *ctx_lens_host, int32_t *per_out,
+                        int32_t *total_out, int32_t *segments_out, int32_t *n_segments);
 int32_t rollattn_plan_capacity(const rollattn_desc *desc);
+int32_t rollattn_plan_workers(const rollattn_desc *desc);
 
-/* Copies the plan the last attn_decode call left in `workspace` back to the host in the
- * format of rollattn_debug_plan (synchronises the stream).  ctx_lens is the same device
- * array that call was given. */
-int rollattn_debug_read_plan(const rollattn_desc *desc, const void *workspace, const int32_t *ctx_lens,
-                             int32_t *chunk_out, int32_t *items_out, int32_t *n_items, void *hip_stream);
+/* Copies the plan the last attn_decode call left in `workspace` back to the host
+ * (synchronises the stream): per, T, and 4 int32 per worker, (b, r, block, blocks in that
+ * row) of the first block of its run, or (-1, -1, -1, 0) for a worker without blocks.
+ * starts_out must hold 4 * rollattn_plan_workers(desc) int32. */
+int rollattn_debug_read_plan(const rollattn_desc *desc, const void *workspace, int32_t *per_out,
+                             int32_t *total_out, int32_t *starts_out, void *hip_stream);
 
 /* Optional per-kernel timing.  While enabled, attn_decode / attn_append bracket their
  * main kernel (not the planning or merge kernels) with HIP events on the call's stream;

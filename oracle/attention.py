@@ -200,36 +200,44 @@ def combine_partials(ms, ls, os_):
 
 # ----------------------------------------------------------------------------------
 # Integer structure of the partition over the KV length (compared bit for bit with the
-# library's plan).  The rule is this package's own statement of it.
+# library's plan).  The rule is stated here by brute enumeration of the block sequence.
 # ----------------------------------------------------------------------------------
 
-def split_plan(ctx_lens, num_kv_heads, *, item_budget=16384, min_chunk=256, max_doublings=8):
-    """Decode split plan.  Every trajectory's range [0, L_b) is cut into pieces of C
-    tokens (the last one ragged); C is the smallest of min_chunk * 2**k, k = 0..
-    max_doublings, for which the number of pieces sum_b ceil(L_b / C) does not exceed
-    cap = max(B, item_budget // Hkv); when none qualifies every trajectory is one piece
-    (C = 0 is reported).  Rows with L_b = 0 have no piece.  Returns (C, items) with
-    items an int32 array [n_items, 4] of (b, start, length, split_index), ordered by b
-    then start, and the per-trajectory piece counts."""
+def split_plan(ctx_lens, rows_per_b, workers, block_tokens=32):
+    """Decode partition.  Trajectory b has n_b = ceil(L_b / block_tokens) blocks; the rows
+    (b, r), r in [0, rows_per_b), are laid end to end with b outermost, n_b blocks each; the
+    resulting sequence of T blocks is dealt to the workers in equal contiguous runs of
+    per = max(1, ceil(T / workers)) blocks.  Returns (per, T, starts, segments): starts is
+    int32 [workers, 4] with the (b, r, block, n_b) each run begins at (-1, -1, -1, 0 for
+    workers without blocks); segments is int32 [n, 6] with one line per maximal piece of a row
+    inside one run, in worker order: (worker, b, r, first block, block count, slot) where slot
+    is -1 if the piece is the whole row, else 0 if it is the first piece of the run, else 1."""
     lens = np.asarray(ctx_lens, dtype=np.int64)
-    cap = max(len(lens), item_budget // num_kv_heads)
-    chosen = 0
-    for k in range(max_doublings + 1):
-        c = min_chunk << k
-        if int(((lens + c - 1) // c).sum()) <= cap:
-            chosen = c
-            break
-    items = []
-    counts = np.zeros(len(lens), dtype=np.int32)
-    for b, length in enumerate(lens.tolist()):
-        if length == 0:
+    n_blocks = (lens + block_tokens - 1) // block_tokens
+    # global position of every block: rows in (b, r) order
+    rows = [(b, r) for b in range(len(lens)) for r in range(rows_per_b) if n_blocks[b] > 0]
+    seq = [(b, r, k) for (b, r) in rows for k in range(int(n_blocks[b]))]
+    total = len(seq)
+    per = max(1, -(-total // workers))
+    starts = np.zeros((workers, 4), dtype=np.int32)
+    starts[:, :3] = -1
+    segments = []
+    for w in range(workers):
+        run = seq[w * per:(w + 1) * per]
+        if not run:
             continue
-        c = chosen if chosen else length
-        n = (length + c - 1) // c
-        counts[b] = n
-        for s in range(n):
-            items.append((b, s * c, min(c, length - s * c), s))
-    return chosen, np.asarray(items, dtype=np.int32).reshape(-1, 4), counts
+        b, r, k = run[0]
+        starts[w] = (b, r, k, n_blocks[b])
+        pieces = []
+        for (b, r, k) in run:
+            if pieces and pieces[-1][0] == b and pieces[-1][1] == r:
+                pieces[-1][3] += 1
+            else:
+                pieces.append([b, r, k, 1])
+        for i, (b, r, k, cnt) in enumerate(pieces):
+            whole = k == 0 and cnt == n_blocks[b]
+            segments.append((w, b, r, k, cnt, -1 if whole else (0 if i == 0 else 1)))
+    return per, total, starts, np.asarray(segments, dtype=np.int32).reshape(-1, 6)
 
 
 def append_tile_plan(q_lens, tile_tokens):

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "librollattn.so")
 F32, BF16, FP8_E4M3 = 0, 1, 2
 EXPORTS = (
     "attn_decode", "attn_append", "rollattn_workspace_bytes", "rollattn_debug_gather",
-    "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_debug_read_plan",
+    "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan",
     "rollattn_profile_enable", "rollattn_profile_read", "rollattn_status_string",
     "rollattn_last_hip_error", "rollattn_version",
 )
@@ -66,11 +66,13 @@ def lib() -> ctypes.CDLL:
         l.rollattn_workspace_bytes.restype = ctypes.c_size_t
         l.rollattn_debug_gather.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp]
         l.rollattn_debug_gather.restype = ctypes.c_int
-        l.rollattn_debug_plan.argtypes = [dp, i32p, i32p, i32p, i32p]
+        l.rollattn_debug_plan.argtypes = [dp, i32p, i32p, i32p, i32p, i32p]
         l.rollattn_debug_plan.restype = ctypes.c_int
         l.rollattn_plan_capacity.argtypes = [dp]
         l.rollattn_plan_capacity.restype = ctypes.c_int32
-        l.rollattn_debug_read_plan.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp]
+        l.rollattn_plan_workers.argtypes = [dp]
+        l.rollattn_plan_workers.restype = ctypes.c_int32
+        l.rollattn_debug_read_plan.argtypes = [dp, vp, i32p, i32p, i32p, vp]
         l.rollattn_debug_read_plan.restype = ctypes.c_int
         l.rollattn_profile_enable.argtypes = [ctypes.c_int]
         l.rollattn_profile_enable.restype = ctypes.c_int
@@ -185,32 +187,36 @@ def debug_gather(pages, page_table, ctx_lens, b, kv_head, length, stream=None) -
 
 
 def debug_plan(desc: Desc, ctx_lens_host: np.ndarray):
-    """Host twin of the decode partition: (chunk, items [n, 4] int32)."""
+    """Host twin of the decode partition: (per, total, segments [n, 6] int32)."""
     l = lib()
     cap = int(l.rollattn_plan_capacity(ctypes.byref(desc)))
     lens = np.ascontiguousarray(ctx_lens_host, dtype=np.int32)
-    items = np.zeros((max(cap, 1), 4), dtype=np.int32)
-    chunk, n = ctypes.c_int32(0), ctypes.c_int32(0)
+    segs = np.zeros((max(cap, 1), 6), dtype=np.int32)
+    per, total, n = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
     i32p = ctypes.POINTER(ctypes.c_int32)
-    rc = l.rollattn_debug_plan(ctypes.byref(desc), lens.ctypes.data_as(i32p), ctypes.byref(chunk),
-                               items.ctypes.data_as(i32p), ctypes.byref(n))
+    rc = l.rollattn_debug_plan(ctypes.byref(desc), lens.ctypes.data_as(i32p), ctypes.byref(per), ctypes.byref(total),
+                               segs.ctypes.data_as(i32p), ctypes.byref(n))
     if rc:
         raise RollattnError(rc, "rollattn_debug_plan")
-    return int(chunk.value), items[: n.value].copy()
+    return int(per.value), int(total.value), segs[: n.value].copy()
 
 
-def read_plan(desc: Desc, workspace: torch.Tensor, ctx_lens: torch.Tensor, stream=None):
-    """The plan the last attn_decode call left in `workspace`: (chunk, items [n, 4] int32)."""
+def plan_workers(desc: Desc) -> int:
+    return int(lib().rollattn_plan_workers(ctypes.byref(desc)))
+
+
+def read_plan(desc: Desc, workspace: torch.Tensor, stream=None):
+    """The plan the last attn_decode call left in `workspace`: (per, total, starts [W, 4] int32)."""
     l = lib()
-    cap = int(l.rollattn_plan_capacity(ctypes.byref(desc)))
-    items = np.zeros((max(cap, 1), 4), dtype=np.int32)
-    chunk, n = ctypes.c_int32(0), ctypes.c_int32(0)
+    workers = plan_workers(desc)
+    starts = np.zeros((max(workers, 1), 4), dtype=np.int32)
+    per, total = ctypes.c_int32(0), ctypes.c_int32(0)
     i32p = ctypes.POINTER(ctypes.c_int32)
-    rc = l.rollattn_debug_read_plan(ctypes.byref(desc), _ptr(workspace), _ptr(ctx_lens), ctypes.byref(chunk),
-                                    items.ctypes.data_as(i32p), ctypes.byref(n), _stream(stream))
+    rc = l.rollattn_debug_read_plan(ctypes.byref(desc), _ptr(workspace), ctypes.byref(per), ctypes.byref(total),
+                                    starts.ctypes.data_as(i32p), _stream(stream))
     if rc:
         raise RollattnError(rc, "rollattn_debug_read_plan")
-    return int(chunk.value), items[: n.value].copy()
+    return int(per.value), int(total.value), starts
 
 
 def profile_enable(on: bool) -> None:

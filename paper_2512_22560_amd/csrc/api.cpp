@@ -53,8 +53,6 @@ int check_desc(const rollattn_desc* d, bool need_scales = true) {
   return ROLLATTN_OK;
 }
 
-int32_t plan_cap(const rollattn_desc& d) { return std::max<int32_t>(std::max(d.batch, 1), kItemBudget / d.num_kv_heads); }
-
 struct ProfileScope {
   hipStream_t s;
   bool on = false;
@@ -81,15 +79,18 @@ struct ProfileScope {
 
 WorkspaceLayout decode_layout(const rollattn_desc& d) {
   WorkspaceLayout w{};
-  const size_t group = d.num_q_heads / d.num_kv_heads;
-  w.cap = plan_cap(d);
+  const int group = d.num_q_heads / d.num_kv_heads;
+  const bool f32 = d.q_dtype == ROLLATTN_F32;
+  w.head_tile = f32 ? kF32HeadTile : kMfmaHeadTile;
+  w.rows_per_b = d.num_kv_heads * ((group + w.head_tile - 1) / w.head_tile);
+  w.workers = f32 ? kF32DecodeWgs : kMfmaDecodeWgs * 4;
   size_t off = 0;
   w.header = off;      off += align256(sizeof(int32_t) * kPlanWords);
-  w.item_b = off;      off += align256(sizeof(int32_t) * (size_t)w.cap);
-  w.item_start = off;  off += align256(sizeof(int32_t) * (size_t)w.cap);
-  w.row_first = off;   off += align256(sizeof(int32_t) * ((size_t)d.batch + 1));
-  w.partial_ml = off;  off += align256(sizeof(float) * (size_t)w.cap * d.num_kv_heads * group * 2);
-  w.partial_o = off;   off += align256(sizeof(float) * (size_t)w.cap * d.num_kv_heads * group * d.head_dim);
+  w.prefix = off;      off += align256(sizeof(int32_t) * ((size_t)d.batch + 1));
+  w.wstart = off;      off += align256(sizeof(int32_t) * 4 * (size_t)w.workers);
+  w.tile_q0 = off;
+  w.partial_ml = off;  off += align256(sizeof(float) * 2 * (size_t)w.workers * w.head_tile * 2);
+  w.partial_o = off;   off += align256(sizeof(float) * 2 * (size_t)w.workers * w.head_tile * d.head_dim);
   w.total = off;
   return w;
 }
@@ -98,16 +99,81 @@ WorkspaceLayout append_layout(const rollattn_desc& d, int32_t total_q) {
   WorkspaceLayout w{};
   const int group = d.num_q_heads / d.num_kv_heads;
   const int tile_tokens = std::max(1, kAppendTileRows / group);
-  w.cap = (int32_t)std::min<int64_t>((int64_t)total_q / tile_tokens + d.batch + 1, INT32_MAX);
+  w.workers = (int32_t)std::min<int64_t>((int64_t)total_q / tile_tokens + d.batch + 1, INT32_MAX);
   size_t off = 0;
   w.header = off;      off += align256(sizeof(int32_t) * kPlanWords);
-  w.item_b = off;      off += align256(sizeof(int32_t) * (size_t)w.cap);
-  w.item_start = off;  off += align256(sizeof(int32_t) * (size_t)w.cap);
-  w.row_first = off;
+  w.wstart = off;      off += align256(sizeof(int32_t) * (size_t)w.workers);
+  w.tile_q0 = off;     off += align256(sizeof(int32_t) * (size_t)w.workers);
+  w.prefix = off;
   w.partial_ml = off;
   w.partial_o = off;
   w.total = off;
   return w;
+}
+
+// The partition rule on the host (same arithmetic as plan_decode_kernel).
+struct HostPlan {
+  int32_t per = 1, total = 0;
+  std::vector<int32_t> prefix;   // [B + 1]
+};
+
+HostPlan host_plan(const int32_t* lens, int32_t batch, int32_t rows_per_b, int32_t workers) {
+  HostPlan p;
+  p.prefix.resize((size_t)batch + 1);
+  int32_t run = 0;
+  for (int32_t b = 0; b < batch; ++b) {
+    p.prefix[b] = run;
+    run += (lens[b] + kBlockTokens - 1) / kBlockTokens;
+  }
+  p.prefix[batch] = run;
+  p.total = run * rows_per_b;
+  p.per = std::max(1, (p.total + workers - 1) / workers);
+  return p;
+}
+
+// Expands (per, total, prefix) into the row segments each worker walks: 6 int32 per segment,
+// (worker, b, row, first block, block count, slot) with slot = -1 for a whole row (written
+// directly), else the partial slot (0 or 1) the segment's result goes to.
+int32_t expand_segments(const HostPlan& p, int32_t batch, int32_t rows_per_b, int32_t workers, int32_t* out,
+                        int64_t cap_segments) {
+  int64_t n_seg = 0;
+  for (int32_t w = 0; w < workers; ++w) {
+    const int64_t x0 = (int64_t)w * p.per;
+    if (x0 >= p.total) break;
+    int32_t left = (int32_t)std::min<int64_t>(p.per, p.total - x0);
+    // largest b with rows_per_b * prefix[b] <= x0
+    int32_t lo = 0, hi = batch;
+    while (hi - lo > 1) {
+      const int32_t mid = (lo + hi) >> 1;
+      if ((int64_t)rows_per_b * p.prefix[mid] <= x0) lo = mid; else hi = mid;
+    }
+    int32_t b = lo, n = p.prefix[b + 1] - p.prefix[b];
+    const int32_t rem = (int32_t)(x0 - (int64_t)rows_per_b * p.prefix[b]);
+    int32_t r = rem / n, blk = rem % n;
+    bool first = true;
+    while (left > 0) {
+      const int32_t cnt = std::min(left, n - blk);
+      if (out && n_seg < cap_segments) {
+        int32_t* o = out + 6 * n_seg;
+        o[0] = w; o[1] = b; o[2] = r; o[3] = blk; o[4] = cnt;
+        o[5] = (blk == 0 && cnt == n) ? -1 : (first ? 0 : 1);
+      }
+      ++n_seg;
+      first = false;
+      left -= cnt;
+      if (left > 0) {
+        blk = 0;
+        if (++r == rows_per_b) {
+          r = 0;
+          do {
+            ++b;
+            n = p.prefix[b + 1] - p.prefix[b];
+          } while (n == 0);
+        }
+      }
+    }
+  }
+  return (int32_t)std::min<int64_t>(n_seg, INT32_MAX);
 }
 
 }  // namespace rollattn
@@ -122,49 +188,31 @@ size_t rollattn_workspace_bytes(const rollattn_desc* desc, int32_t total_q) {
 }
 
 int32_t rollattn_plan_capacity(const rollattn_desc* desc) {
-  if (check_desc(desc) != ROLLATTN_OK) return 0;
-  return plan_cap(*desc);
+  if (check_desc(desc, false) != ROLLATTN_OK) return 0;
+  const WorkspaceLayout w = decode_layout(*desc);
+  // every worker boundary and every row end closes one segment
+  const int64_t cap = (int64_t)w.workers + (int64_t)desc->batch * w.rows_per_b;
+  return (int32_t)std::min<int64_t>(cap, INT32_MAX);
 }
 
-int rollattn_debug_plan(const rollattn_desc* desc, const int32_t* ctx_lens_host, int32_t* chunk_out,
-                        int32_t* items_out, int32_t* n_items) {
-  int rc = check_desc(desc);
+int rollattn_debug_plan(const rollattn_desc* desc, const int32_t* ctx_lens_host, int32_t* per_out,
+                        int32_t* total_out, int32_t* segments_out, int32_t* n_segments) {
+  int rc = check_desc(desc, false);
   if (rc) return rc;
-  if ((!ctx_lens_host && desc->batch > 0) || !chunk_out || !n_items) return ROLLATTN_EINVAL;
-  const int32_t cap = plan_cap(*desc);
-  int32_t chunk = 0;
-  for (int k = 0; k <= kMaxDoublings; ++k) {
-    const int32_t c = kMinChunk << k;
-    int64_t pieces = 0;
-    for (int32_t b = 0; b < desc->batch; ++b) pieces += (ctx_lens_host[b] + c - 1) / c;
-    if (pieces <= cap) {
-      chunk = c;
-      break;
-    }
-  }
-  int32_t n = 0;
-  for (int32_t b = 0; b < desc->batch; ++b) {
-    const int32_t len = ctx_lens_host[b];
-    const int32_t count = chunk ? (len + chunk - 1) / chunk : (len > 0 ? 1 : 0);
-    for (int32_t s = 0; s < count; ++s, ++n) {
-      if (items_out) {
-        items_out[4 * n + 0] = b;
-        items_out[4 * n + 1] = s * chunk;
-        items_out[4 * n + 2] = chunk ? std::min(chunk, len - s * chunk) : len;
-        items_out[4 * n + 3] = s;
-      }
-    }
-  }
-  *chunk_out = chunk;
-  *n_items = n;
+  if ((!ctx_lens_host && desc->batch > 0) || !per_out || !total_out || !n_segments) return ROLLATTN_EINVAL;
+  const WorkspaceLayout w = decode_layout(*desc);
+  const HostPlan p = host_plan(ctx_lens_host, desc->batch, w.rows_per_b, w.workers);
+  *per_out = p.per;
+  *total_out = p.total;
+  *n_segments = expand_segments(p, desc->batch, w.rows_per_b, w.workers, segments_out, rollattn_plan_capacity(desc));
   return ROLLATTN_OK;
 }
 
-int rollattn_debug_read_plan(const rollattn_desc* desc, const void* workspace, const int32_t* ctx_lens,
-                             int32_t* chunk_out, int32_t* items_out, int32_t* n_items, void* hip_stream) {
-  int rc = check_desc(desc);
+int rollattn_debug_read_plan(const rollattn_desc* desc, const void* workspace, int32_t* per_out,
+                             int32_t* total_out, int32_t* starts_out, void* hip_stream) {
+  int rc = check_desc(desc, false);
   if (rc) return rc;
-  if (!workspace || !ctx_lens || !chunk_out || !n_items) return ROLLATTN_EINVAL;
+  if (!workspace || !per_out || !total_out || !starts_out) return ROLLATTN_EINVAL;
   const WorkspaceLayout w = decode_layout(*desc);
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = hipStreamSynchronize(s);
@@ -172,25 +220,17 @@ int rollattn_debug_read_plan(const rollattn_desc* desc, const void* workspace, c
   const char* base = (const char*)workspace;
   int32_t header[kPlanWords];
   e = hipMemcpy(header, base + w.header, sizeof(header), hipMemcpyDeviceToHost);
+  if (e == hipSuccess)
+    e = hipMemcpy(starts_out, base + w.wstart, sizeof(int32_t) * 4 * (size_t)w.workers, hipMemcpyDeviceToHost);
   if (e != hipSuccess) return fail_hip(e);
-  const int32_t n = header[kPlanItems], chunk = header[kPlanChunk];
-  *chunk_out = chunk;
-  *n_items = n;
-  if (!items_out || n <= 0) return ROLLATTN_OK;
-  std::vector<int32_t> ib(n), is(n), rf((size_t)desc->batch + 1), lens((size_t)desc->batch);
-  e = hipMemcpy(lens.data(), ctx_lens, sizeof(int32_t) * lens.size(), hipMemcpyDeviceToHost);
-  if (e == hipSuccess) e = hipMemcpy(ib.data(), base + w.item_b, sizeof(int32_t) * n, hipMemcpyDeviceToHost);
-  if (e == hipSuccess) e = hipMemcpy(is.data(), base + w.item_start, sizeof(int32_t) * n, hipMemcpyDeviceToHost);
-  if (e == hipSuccess) e = hipMemcpy(rf.data(), base + w.row_first, sizeof(int32_t) * rf.size(), hipMemcpyDeviceToHost);
-  if (e != hipSuccess) return fail_hip(e);
-  for (int32_t i = 0; i < n; ++i) {
-    const int32_t b = ib[i];
-    items_out[4 * i + 0] = b;
-    items_out[4 * i + 1] = is[i];
-    items_out[4 * i + 2] = chunk ? std::min(chunk, lens[b] - is[i]) : lens[b];
-    items_out[4 * i + 3] = i - rf[b];
-  }
+  *per_out = header[kPlanPer];
+  *total_out = header[kPlanTotal];
   return ROLLATTN_OK;
+}
+
+int32_t rollattn_plan_workers(const rollattn_desc* desc) {
+  if (check_desc(desc, false) != ROLLATTN_OK) return 0;
+  return decode_layout(*desc).workers;
 }
 
 int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
@@ -205,36 +245,34 @@ int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, c
     return ROLLATTN_EALIGN;
   const WorkspaceLayout w = decode_layout(*desc);
   if (workspace_bytes < w.total) return ROLLATTN_EWORKSPACE;
+  // the block sequence is indexed with 32-bit integers
+  if ((int64_t)desc->batch * w.rows_per_b * ((int64_t)desc->max_pages_per_seq / 2 + 1) > INT32_MAX) return ROLLATTN_ESHAPE;
 
   hipStream_t s = (hipStream_t)hip_stream;
   char* base = (char*)workspace;
   DecodeArgs a{};
   a.q = q; a.k_pages = k_pages; a.v_pages = v_pages; a.page_table = page_table; a.ctx_lens = ctx_lens;
   a.out = out; a.k_scale = desc->k_scale; a.v_scale = desc->v_scale;
-  a.header = (int32_t*)(base + w.header);
-  a.item_b = (const int32_t*)(base + w.item_b);
-  a.item_start = (const int32_t*)(base + w.item_start);
-  a.row_first = (const int32_t*)(base + w.row_first);
+  a.header = (const int32_t*)(base + w.header);
+  a.prefix = (const int32_t*)(base + w.prefix);
+  a.wstart = (const int32_t*)(base + w.wstart);
   a.partial_ml = (float*)(base + w.partial_ml);
   a.partial_o = (float*)(base + w.partial_o);
   a.batch = desc->batch; a.hq = desc->num_q_heads; a.hkv = desc->num_kv_heads;
   a.group = desc->num_q_heads / desc->num_kv_heads; a.max_pages = desc->max_pages_per_seq;
+  a.head_tile = w.head_tile; a.rows_per_b = w.rows_per_b;
   a.scale_log2 = desc->sm_scale * 1.4426950408889634f;
 
-  hipError_t e = launch_plan_decode(ctx_lens, desc->batch, w.cap, a.header, (int32_t*)(base + w.item_b),
-                                    (int32_t*)(base + w.item_start), (int32_t*)(base + w.row_first), s);
+  hipError_t e = launch_plan_decode(ctx_lens, desc->batch, w.rows_per_b, w.workers, (int32_t*)(base + w.header),
+                                    (int32_t*)(base + w.prefix), (int32_t*)(base + w.wstart), s);
   if (e != hipSuccess) return fail_hip(e);
   const bool f32 = desc->q_dtype == ROLLATTN_F32;
   {
     ProfileScope prof(s);
     if (f32) {
-      const int tiles = (a.group + 3) / 4;
-      const int grid = (int)std::min<int64_t>((int64_t)w.cap * a.hkv * tiles, kNumCUs * 4);
-      e = launch_decode_f32(a, desc->head_dim, grid, s);
+      e = launch_decode_f32(a, desc->head_dim, kF32DecodeWgs, s);
     } else {
-      const int tiles = (a.group + 15) / 16;
-      const int grid = (int)std::min<int64_t>((int64_t)w.cap * a.hkv * tiles, kNumCUs * 2);
-      e = launch_decode_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, grid, s);
+      e = launch_decode_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, kMfmaDecodeWgs, s);
     }
     prof.stop();
   }
@@ -268,8 +306,8 @@ int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q
   a.q = q_chunk; a.k_pages = k_pages; a.v_pages = v_pages; a.page_table = page_table; a.ctx_lens = ctx_lens;
   a.q_lens = q_lens; a.q_offsets = q_offsets; a.out = out; a.k_scale = desc->k_scale; a.v_scale = desc->v_scale;
   a.header = (int32_t*)(base + w.header);
-  a.tile_b = (const int32_t*)(base + w.item_b);
-  a.tile_q0 = (const int32_t*)(base + w.item_start);
+  a.tile_b = (const int32_t*)(base + w.wstart);
+  a.tile_q0 = (const int32_t*)(base + w.tile_q0);
   a.batch = desc->batch; a.hq = desc->num_q_heads; a.hkv = desc->num_kv_heads;
   a.group = desc->num_q_heads / desc->num_kv_heads; a.max_pages = desc->max_pages_per_seq;
   a.tile_tokens = std::max(1, kAppendTileRows / a.group);
@@ -286,12 +324,12 @@ int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q
     if (e != hipSuccess) return fail_hip(e);
     return ROLLATTN_OK;
   }
-  e = launch_plan_append(q_lens, desc->batch, a.tile_tokens, w.cap, a.header, (int32_t*)(base + w.item_b),
-                         (int32_t*)(base + w.item_start), s);
+  e = launch_plan_append(q_lens, desc->batch, a.tile_tokens, w.workers, a.header, (int32_t*)(base + w.wstart),
+                         (int32_t*)(base + w.tile_q0), s);
   if (e != hipSuccess) return fail_hip(e);
   {
     ProfileScope prof(s);
-    const int grid = (int)std::min<int64_t>((int64_t)w.cap * a.hkv, INT32_MAX);
+    const int grid = (int)std::min<int64_t>((int64_t)w.workers * a.hkv, INT32_MAX);
     e = launch_append_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, grid, s);
     prof.stop();
   }

@@ -12,7 +12,7 @@ namespace rollattn {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kHT = 4;   // query heads per work item
+constexpr int kHT = kF32HeadTile;   // query heads per row
 
 template <int D>
 struct F32Geo {
@@ -98,6 +98,8 @@ __device__ void attend_f32(const float* const* qrows, int n_heads, const float* 
   __syncthreads();
 }
 
+// Decode in float32: every workgroup is one worker of the block partition (see plan.hip) and walks
+// its run of 32-token blocks one row segment at a time.
 template <int D>
 __global__ __launch_bounds__(kThreads) void decode_f32_kernel(const DecodeArgs a) {
   using G_ = F32Geo<D>;
@@ -105,47 +107,59 @@ __global__ __launch_bounds__(kThreads) void decode_f32_kernel(const DecodeArgs a
   __shared__ float ml_part[G_::kGroups][kHT][2];
   __shared__ __attribute__((aligned(16))) float o_out[kHT][D];
   __shared__ float ml_out[kHT][2];
-  __shared__ int item_s;
   const int tid = threadIdx.x;
-  const int group = a.group, hkv = a.hkv;
-  const int n_ht = (group + kHT - 1) / kHT;
-  const int n_work = a.header[kPlanItems] * hkv * n_ht;
-  const int chunk = a.header[kPlanChunk];
-  for (;;) {
-    if (tid == 0) item_s = atomicAdd(&a.header[kPlanCounter], 1);
-    __syncthreads();
-    const int work = item_s;
-    if (work >= n_work) break;
-    const int piece = work / (hkv * n_ht);
-    const int g = (work - piece * hkv * n_ht) / n_ht;
-    const int h0 = (work % n_ht) * kHT;
-    const int n_heads = min(kHT, group - h0);
-    const int b = a.item_b[piece];
-    const int start = a.item_start[piece];
+  const int group = a.group, hkv = a.hkv, rows_per_b = a.rows_per_b;
+  const int n_ht = rows_per_b / hkv;
+  const int worker = blockIdx.x;
+  const int per = a.header[kPlanPer];
+  const int total = a.header[kPlanTotal];
+  if ((long)worker * per >= total) return;
+  int left = min(per, total - worker * per);
+  const int4 st = *(const int4*)(a.wstart + 4 * worker);
+  int b = st.x, r = st.y, blk = st.z, n = st.w;
+  bool first_segment = true;
+  while (left > 0) {
+    const int cnt = min(left, n - blk);                 // blocks of this row that are ours
     const int ctx = a.ctx_lens[b];
-    const int len = chunk ? min(chunk, ctx - start) : ctx;
-    const int n_pieces = a.row_first[b + 1] - a.row_first[b];
+    const int tok0 = blk * kBlockTokens;
+    const int len = min(ctx, (blk + cnt) * kBlockTokens) - tok0;
+    const int g = r / n_ht;
+    const int h0 = (r - g * n_ht) * kHT;
+    const int n_heads = min(kHT, group - h0);
     const float* qrows[kHT];
 #pragma unroll
     for (int h = 0; h < kHT; ++h)
       qrows[h] = (const float*)a.q + ((size_t)b * a.hq + (size_t)g * group + h0 + min(h, n_heads - 1)) * D;
     attend_f32<D>(qrows, n_heads, (const float*)a.k_pages, (const float*)a.v_pages,
-                  a.page_table + (size_t)b * a.max_pages + start / kPageSize, len, hkv, g, a.scale_log2, o_part,
+                  a.page_table + (size_t)b * a.max_pages + tok0 / kPageSize, len, hkv, g, a.scale_log2, o_part,
                   ml_part, o_out, ml_out);
+    const bool whole = (blk == 0 && cnt == n);
     for (int e = tid; e < n_heads * D; e += kThreads) {
       const int h = e / D, d = e % D;
-      if (n_pieces == 1) {
+      if (whole) {
         ((float*)a.out)[((size_t)b * a.hq + (size_t)g * group + h0 + h) * D + d] = o_out[h][d] / ml_out[h][1];
       } else {
-        const size_t slot = (size_t)piece * hkv + g;
-        a.partial_o[(slot * group + h0 + h) * D + d] = o_out[h][d];
+        const size_t slot = (size_t)worker * 2 + (first_segment ? 0 : 1);
+        a.partial_o[(slot * kHT + h) * D + d] = o_out[h][d];
         if (d == 0) {
-          a.partial_ml[(slot * group + h0 + h) * 2 + 0] = ml_out[h][0];
-          a.partial_ml[(slot * group + h0 + h) * 2 + 1] = ml_out[h][1];
+          a.partial_ml[(slot * kHT + h) * 2 + 0] = ml_out[h][0];
+          a.partial_ml[(slot * kHT + h) * 2 + 1] = ml_out[h][1];
         }
       }
     }
     __syncthreads();
+    first_segment = false;
+    left -= cnt;
+    if (left > 0) {                                      // next row of the sequence
+      blk = 0;
+      if (++r == rows_per_b) {
+        r = 0;
+        do {
+          ++b;
+          n = a.prefix[b + 1] - a.prefix[b];
+        } while (n == 0);
+      }
+    }
   }
 }
 

@@ -1,8 +1,13 @@
-// Split-K merge: one wave per (trajectory, query head) folds the per-piece partial results
-// (max m_s in log2 units, sum l_s, un-normalised o_s) into the final row:
+// Split-K merge: one wave per (trajectory, query head) folds the partial results that the
+// decode workers left for rows they did not cover alone (max m_s in log2 units, sum l_s,
+// un-normalised o_s) into the final row:
 //   M = max_s m_s ;  out = sum_s 2^(m_s - M) o_s / sum_s 2^(m_s - M) l_s
-// which equals the softmax over the whole context.  Rows with a single piece were already
-// written by the main kernel; rows with no piece (empty context) are zero-filled here.
+// which equals the softmax over the whole context.  Which workers touched a row follows from
+// the plan alone: the row occupies blocks [R0, R1) of the global sequence and worker w owns
+// [w * per, (w + 1) * per).  A worker keeps at most two partials, slot 0 for the first row
+// segment of its run and slot 1 for the last; the only segment that lands in slot 1 is the one
+// of the worker whose run began before this row.  Rows covered by a single worker were already
+// written by it; rows without tokens are zero-filled here.
 #include "rollattn_internal.h"
 
 namespace rollattn {
@@ -20,29 +25,39 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const DecodeArgs a) {
   if (row >= (long)a.batch * a.hq) return;
   const int b = (int)(row / a.hq);
   const int h = (int)(row % a.hq);
-  const int first = a.row_first[b];
-  const int n = a.row_first[b + 1] - first;
-  if (n == 1) return;
+  const int ht = a.head_tile;
+  const int n_ht = a.rows_per_b / a.hkv;
+  const int g = h / a.group, j = h % a.group;
+  const int r = g * n_ht + j / ht, jj = j % ht;
+  const int per = a.header[kPlanPer];
+  const int first = a.prefix[b];
+  const int n = a.prefix[b + 1] - first;
+  const long r0 = (long)a.rows_per_b * first + (long)r * n;
+  const int wf = n ? (int)(r0 / per) : 0;
+  const int wl = n ? (int)((r0 + n - 1) / per) : 0;
+  if (n && wf == wl) return;      // one worker had the whole row
   float o[kPer];
 #pragma unroll
   for (int e = 0; e < kPer; ++e) o[e] = 0.f;
   float inv = 0.f;
-  if (n > 1) {
-    const int g = h / a.group, j = h % a.group;
+  if (n) {
+    const int first_slot = ((long)wf * per < r0) ? 1 : 0;
+    const int pieces = wl - wf + 1;
     float mmax = -INFINITY;
-    for (int s = lane; s < n; s += 64) {
-      const size_t slot = (size_t)(first + s) * a.hkv + g;
-      mmax = fmaxf(mmax, a.partial_ml[(slot * a.group + j) * 2]);
+    for (int s = lane; s < pieces; s += 64) {
+      const size_t slot = (size_t)(wf + s) * 2 + (s == 0 ? first_slot : 0);
+      mmax = fmaxf(mmax, a.partial_ml[(slot * ht + jj) * 2]);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, off, 64));
     float lsum = 0.f;
-    for (int s = 0; s < n; ++s) {
-      const size_t slot = (size_t)(first + s) * a.hkv + g;
-      const float* ml = a.partial_ml + (slot * a.group + j) * 2;
+#pragma unroll 4
+    for (int s = 0; s < pieces; ++s) {
+      const size_t slot = (size_t)(wf + s) * 2 + (s == 0 ? first_slot : 0);
+      const float* ml = a.partial_ml + (slot * ht + jj) * 2;
       const float f = __builtin_amdgcn_exp2f(ml[0] - mmax);
       lsum += f * ml[1];
-      const float* src = a.partial_o + (slot * a.group + j) * D + lane * kPer;
+      const float* src = a.partial_o + (slot * ht + jj) * D + lane * kPer;
 #pragma unroll
       for (int e = 0; e < kPer; ++e) o[e] += f * src[e];
     }

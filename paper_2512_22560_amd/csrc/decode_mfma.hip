@@ -1,13 +1,16 @@
 // Decode attention for bf16 queries over bf16 or FP8-E4M3 paged KV (gfx950).
 //
-// One work item = (piece of one trajectory's KV range, KV head).  All G query heads of
-// the group ride along as the 16 columns of an MFMA tile, so K and V are read from HBM
-// exactly once per item.  Workgroups are persistent and pull items from an atomic
-// counter.  Inside a workgroup every wave owns whole 32-token blocks (two pages): it
-// prefetches them from HBM with 16-byte loads into registers several blocks ahead,
-// drops them into its private LDS tile, and consumes them with
+// A row is (trajectory, KV head, tile of up to 16 query heads of its group): the heads ride
+// along as the 16 columns of an MFMA tile, so K and V are read from HBM exactly once per
+// row.  Rows are cut into 32-token blocks (two pages), laid end to end, and every wave of
+// the launch is a worker that owns one equal, contiguous run of that block sequence (the
+// plan kernel tells it where its run starts).  A wave streams its run without any
+// workgroup-level synchronisation: it prefetches blocks from HBM with 16-byte loads into
+// registers several blocks ahead, drops each into its private LDS tile, and consumes it with
 //   S^T = K Q^T          (tokens x heads, v_mfma_f32_16x16x32_bf16, K rows as A)
 //   O^T += V^T P^T       (dims x heads, V read back transposed with ds_read_b64_tr_*)
+// A run that covers a whole row writes the row's output itself; a run that starts or ends
+// inside a row leaves an un-normalised partial (max, sum, O) for the merge kernel.
 // The transposed products keep "head" on the lane axis in both results, so the online
 // softmax state (running max, running sum, rescale factor) is one scalar per lane and P
 // feeds the second product straight from the first one's accumulator registers.
@@ -28,7 +31,6 @@ typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kBlockTokens = 32;   // tokens a wave consumes per step (two pages)
 
 template <int D, bool FP8>
 struct Geo {
@@ -77,288 +79,282 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16(uint32_t lo, uint32_t hi) {
   return r;
 }
 
-template <int D, bool FP8>
-__global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeArgs a) {
-  using G_ = Geo<D, FP8>;
-  // Per wave: one K tile and one V tile; reused at the end of an item to merge the waves.
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves][2 * G_::kTileBytes];
-  __shared__ float ml_s[kWaves][16][2];
-  __shared__ int item_s;
-  static_assert(2 * G_::kTileBytes >= 16 * D * 4, "wave tile must hold a 16 x D float block for the merge");
+struct Cursor {
+  int b, r, blk;   // trajectory, row within it, block within the row
+  int n, len;      // blocks in the row, context length of the trajectory
+};
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+template <int D, bool FP8>
+__global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const DecodeArgs a) {
+  using G_ = Geo<D, FP8>;
+  // Per wave: one K tile and one V tile.
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves][2 * G_::kTileBytes];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r16 = lane & 15;   // MFMA row / column index carried by this lane
   const int q4 = lane >> 4;    // which quarter of the contraction this lane feeds
   unsigned char* const k_lds = lds[wave];
   unsigned char* const v_lds = lds[wave] + G_::kTileBytes;
 
-  const int group = a.group;
-  const int hkv = a.hkv;
-  const int n_ht = (group + 15) >> 4;          // 16-head tiles per KV head (1 unless G > 16)
-  const int n_work = a.header[kPlanItems] * hkv * n_ht;
-  const int chunk = a.header[kPlanChunk];
+  const int worker = blockIdx.x * kWaves + wave;
+  const int per = a.header[kPlanPer];
+  const int total = a.header[kPlanTotal];
+  if ((long)worker * per >= total) return;
+  const int n_mine = min(per, total - worker * per);
+  const int group = a.group, hkv = a.hkv, rows_per_b = a.rows_per_b;
+  const int n_ht = rows_per_b / hkv;
   const size_t tile_stride = (size_t)kPageSize * G_::kRowBytes;   // bytes of one (page, head) tile
 
-  for (;;) {
-    if (tid == 0) item_s = atomicAdd(&a.header[kPlanCounter], 1);
-    __syncthreads();
-    const int work = item_s;
-    if (work >= n_work) break;
-    const int piece = work / (hkv * n_ht);
-    const int g = (work - piece * hkv * n_ht) / n_ht;
-    const int h0 = (work % n_ht) << 4;          // first head of the group handled here
-    const int b = a.item_b[piece];
-    const int start = a.item_start[piece];
-    const int ctx = a.ctx_lens[b];
-    const int len = chunk ? min(chunk, ctx - start) : ctx;       // tokens of this piece
-    const int n_pieces = a.row_first[b + 1] - a.row_first[b];
-    const int n_blocks = (len + kBlockTokens - 1) / kBlockTokens;
-    // This wave takes blocks wave, wave + 4, ...
-    const int my_blocks = (n_blocks - wave + kWaves - 1) / kWaves;
-    const int32_t* table = a.page_table + (size_t)b * a.max_pages + start / kPageSize;
-    const int live_pages = (len + kPageSize - 1) / kPageSize;
+  Cursor pc;   // producer: next block to request from HBM
+  {
+    const int4 st = *(const int4*)(a.wstart + 4 * worker);
+    pc.b = __builtin_amdgcn_readfirstlane(st.x);
+    pc.r = __builtin_amdgcn_readfirstlane(st.y);
+    pc.blk = __builtin_amdgcn_readfirstlane(st.z);
+    pc.n = __builtin_amdgcn_readfirstlane(st.w);
+    pc.len = a.ctx_lens[pc.b];
+  }
+  Cursor cc = pc;   // consumer: block being computed
+  auto advance = [&](Cursor& c) {
+    if (++c.blk < c.n) return;
+    c.blk = 0;
+    if (++c.r < rows_per_b) return;
+    c.r = 0;
+    do {
+      ++c.b;
+      c.n = a.prefix[c.b + 1] - a.prefix[c.b];
+    } while (c.n == 0);
+    c.len = a.ctx_lens[c.b];
+  };
 
-    // Q^T as the B operand: lane (head r16, quarter q4) holds 8 consecutive dims per step.
-    bf16x8 qop[G_::kKK];
-    {
-      const __bf16* qrow = (const __bf16*)a.q + ((size_t)b * a.hq + (size_t)g * group + h0 + r16) * D;
-#pragma unroll
-      for (int kk = 0; kk < G_::kKK; ++kk) {
-        bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (h0 + r16 < group) {
-          if (FP8) {
-            // 16-byte K chunks hold 16 dims; step 2p+e uses bytes e*8.. of chunk p*4+q4
-            v = *(const bf16x8*)(qrow + ((kk >> 1) * 4 + q4) * 16 + (kk & 1) * 8);
-          } else {
-            v = *(const bf16x8*)(qrow + (kk * 4 + q4) * 8);
-          }
-        }
-        qop[kk] = v;
-      }
+  // ---- producer state: a window of 64 page ids (32 blocks) of the current row, one per lane
+  int pwin = -1, pid_vec = 0, pid_next = 0;
+  int issued = 0;
+  uint4 kreg[G_::kStages][G_::kLoads];
+  uint4 vreg[G_::kStages][G_::kLoads];
+  float ksc[G_::kStages], vsc[G_::kStages];   // FP8: page scales of this lane's 8 tokens
+  auto load_window = [&](int k) {
+    const int pg = k * 64 + lane;
+    return (pg < ((pc.len + kPageSize - 1) >> 4)) ? a.page_table[(size_t)pc.b * a.max_pages + pg] : 0;
+  };
+  auto issue = [&](int stage) {
+    const int k = pc.blk >> 5;
+    if (k != pwin) {
+      pid_vec = (pwin >= 0 && k == pwin + 1) ? pid_next : load_window(k);
+      pid_next = load_window(k + 1);
+      pwin = k;
     }
+    const int g = pc.r / n_ht;
+    const int tok0 = pc.blk * kBlockTokens;
+    const int p0 = __builtin_amdgcn_readlane(pid_vec, ((pc.blk & 31) << 1));
+    const int p1 = __builtin_amdgcn_readlane(pid_vec, ((pc.blk & 31) << 1) + 1);
+    if (FP8) {
+      const int pid = (q4 < 2) ? p0 : p1;        // tokens 0-15 of the block sit in its first page
+      ksc[stage] = a.k_scale[pid];
+      vsc[stage] = a.v_scale[pid];
+    }
+#pragma unroll
+    for (int j = 0; j < G_::kLoads; ++j) {
+      const int row0 = j * G_::kRowsPerLoad;                 // first token row of this load
+      const int pid = (row0 < kPageSize) ? p0 : p1;
+      const size_t off = ((size_t)pid * hkv + g) * tile_stride + (size_t)(row0 % kPageSize) * G_::kRowBytes +
+                         (size_t)lane * 16;
+      const int row = row0 + lane / G_::kChunks;
+      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+      if (tok0 + row < pc.len) {
+        kv = *(const uint4*)((const unsigned char*)a.k_pages + off);
+        vv = *(const uint4*)((const unsigned char*)a.v_pages + off);
+      }
+      kreg[stage][j] = kv;
+      vreg[stage][j] = vv;
+    }
+    // step to the next block of the run (never past its end: the rows after the last block need
+    // not exist); a new row starts with a fresh page-id window
+    if (++issued < n_mine) {
+      const int row_before = pc.b * rows_per_b + pc.r;
+      advance(pc);
+      if (pc.b * rows_per_b + pc.r != row_before) pwin = -1;
+    }
+  };
+  auto commit = [&](int stage) {
+#pragma unroll
+    for (int j = 0; j < G_::kLoads; ++j) {
+      const int row = j * G_::kRowsPerLoad + lane / G_::kChunks;
+      const int c = lane % G_::kChunks;
+      const int kc = (c ^ key_k(row)) & (G_::kChunks - 1);
+      const int vc = (c ^ (FP8 ? key_v8(row) : key_v16(row))) & (G_::kChunks - 1);
+      *(uint4*)(k_lds + row * G_::kRowBytes + kc * 16) = kreg[stage][j];
+      *(uint4*)(v_lds + row * G_::kRowBytes + vc * 16) = vreg[stage][j];
+    }
+  };
 
-    floatx4 acc[G_::kDT];
+  // ---- consumer state
+  bf16x8 qop[G_::kKK];       // Q^T as the B operand: lane (head r16, quarter q4), 8 dims per step
+  floatx4 acc[G_::kDT];      // O^T: lane (head r16, quarter q4) holds dims dt*16 + q4*4 + (0..3)
+  float m_run = -INFINITY;   // running max (log2 units) of this lane's head
+  float l_run = 0.f;         // this lane's share of the running sum
+  int seg_first_blk = 0;     // block of the row at which the current segment started
+  bool first_segment = true;
+
+  auto begin_segment = [&]() {
+    const int g = cc.r / n_ht;
+    const int h0 = (cc.r - g * n_ht) * kMfmaHeadTile;
+    const __bf16* qrow = (const __bf16*)a.q + ((size_t)cc.b * a.hq + (size_t)g * group + h0 + r16) * D;
+#pragma unroll
+    for (int kk = 0; kk < G_::kKK; ++kk) {
+      bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (h0 + r16 < group) {
+        if (FP8) {
+          // 16-byte K chunks hold 16 dims; step 2p+e uses bytes e*8.. of chunk p*4+q4
+          v = *(const bf16x8*)(qrow + ((kk >> 1) * 4 + q4) * 16 + (kk & 1) * 8);
+        } else {
+          v = *(const bf16x8*)(qrow + (kk * 4 + q4) * 8);
+        }
+      }
+      qop[kk] = v;
+    }
 #pragma unroll
     for (int dt = 0; dt < G_::kDT; ++dt) acc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY;   // running max (log2 units) of this lane's head
-    float l_run = 0.f;         // this lane's share of the running sum
-
-    // Page ids of this wave's blocks: lane j keeps page ((wave + 4*(j/2)) * 2 + (j&1)) of the
-    // current window of 32 blocks.
-    int pid_vec = 0;
-    uint4 kreg[G_::kStages][G_::kLoads];
-    uint4 vreg[G_::kStages][G_::kLoads];
-    float ksc[G_::kStages], vsc[G_::kStages];   // FP8: page scales of this lane's 8 tokens
-
-    auto refill_pages = [&](int first_local_block) {
-      const int pg = ((wave + kWaves * (first_local_block + (lane >> 1))) << 1) + (lane & 1);
-      pid_vec = (pg < live_pages) ? table[pg] : 0;
-    };
-    auto issue = [&](int stage, int i /* local block index */) {
-      const int blk = wave + kWaves * i;
-      const int tok0 = blk * kBlockTokens;
-      const int p0 = __builtin_amdgcn_readlane(pid_vec, ((i & 31) << 1));
-      const int p1 = __builtin_amdgcn_readlane(pid_vec, ((i & 31) << 1) + 1);
+    m_run = -INFINITY;
+    l_run = 0.f;
+    seg_first_blk = cc.blk;
+  };
+  auto end_segment = [&]() {
+    const int g = cc.r / n_ht;
+    const int h0 = (cc.r - g * n_ht) * kMfmaHeadTile;
+    const float l_tot = xor32_add(xor16_add(l_run));
+    const bool head_ok = h0 + r16 < group;
+    if (seg_first_blk == 0 && cc.blk == cc.n - 1) {
+      // the whole row was ours: normalise and store
+      const float inv = 1.f / l_tot;
+      __bf16* dst = (__bf16*)a.out + ((size_t)cc.b * a.hq + (size_t)g * group + h0 + r16) * D + q4 * 4;
+      if (head_ok) {
+#pragma unroll
+        for (int dt = 0; dt < G_::kDT; ++dt) {
+          bf16x4 pk;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(acc[dt][e] * inv);
+          *(bf16x4*)(dst + dt * 16) = pk;
+        }
+      }
+    } else {
+      const size_t slot = (size_t)worker * 2 + (first_segment ? 0 : 1);
+      if (head_ok) {
+        float* dst = a.partial_o + (slot * kMfmaHeadTile + r16) * D + q4 * 4;
+#pragma unroll
+        for (int dt = 0; dt < G_::kDT; ++dt) *(floatx4*)(dst + dt * 16) = acc[dt];
+        if (q4 == 0) {
+          a.partial_ml[(slot * kMfmaHeadTile + r16) * 2 + 0] = m_run;
+          a.partial_ml[(slot * kMfmaHeadTile + r16) * 2 + 1] = l_tot;
+        }
+      }
+    }
+    first_segment = false;
+  };
+  auto compute = [&](float kscale, float vscale) {
+    const int tok0 = cc.blk * kBlockTokens;
+    const int len = cc.len;
+    // ---- S^T = K Q^T for the two 16-row tiles; tile e row r is token (r/4)*8 + e*4 + r%4
+    floatx4 s[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      s[e] = floatx4{0.f, 0.f, 0.f, 0.f};
+      const int t = ((r16 >> 2) << 3) + e * 4 + (r16 & 3);
+      const unsigned char* rowp = k_lds + t * G_::kRowBytes;
+      const int key = key_k(t);
       if (FP8) {
-        const int pid = (q4 < 2) ? p0 : p1;        // tokens 0-15 of the block sit in its first page
-        ksc[stage] = a.k_scale[pid];
-        vsc[stage] = a.v_scale[pid];
-      }
 #pragma unroll
-      for (int j = 0; j < G_::kLoads; ++j) {
-        const int row0 = j * G_::kRowsPerLoad;                 // first token row of this load
-        const int pid = (row0 < kPageSize) ? p0 : p1;
-        const size_t off = ((size_t)pid * hkv + g) * tile_stride + (size_t)(row0 % kPageSize) * G_::kRowBytes +
-                           (size_t)lane * 16;
-        const int row = row0 + lane / G_::kChunks;
-        uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-        if (tok0 + row < len) {
-          kv = *(const uint4*)((const unsigned char*)a.k_pages + off);
-          vv = *(const uint4*)((const unsigned char*)a.v_pages + off);
+        for (int p = 0; p < G_::kChunks / 4; ++p) {
+          const int c = ((p * 4 + q4) ^ key) & (G_::kChunks - 1);
+          const uint4 raw = *(const uint4*)(rowp + c * 16);
+          s[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fp8x8_to_bf16(raw.x, raw.y), qop[2 * p], s[e], 0, 0, 0);
+          s[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fp8x8_to_bf16(raw.z, raw.w), qop[2 * p + 1], s[e], 0, 0, 0);
         }
-        kreg[stage][j] = kv;
-        vreg[stage][j] = vv;
-      }
-    };
-    auto commit = [&](int stage) {
+      } else {
 #pragma unroll
-      for (int j = 0; j < G_::kLoads; ++j) {
-        const int row = j * G_::kRowsPerLoad + lane / G_::kChunks;
-        const int c = lane % G_::kChunks;
-        const int kc = (c ^ key_k(row)) & (G_::kChunks - 1);
-        const int vc = (c ^ (FP8 ? key_v8(row) : key_v16(row))) & (G_::kChunks - 1);
-        *(uint4*)(k_lds + row * G_::kRowBytes + kc * 16) = kreg[stage][j];
-        *(uint4*)(v_lds + row * G_::kRowBytes + vc * 16) = vreg[stage][j];
-      }
-    };
-    auto compute = [&](int stage, int i) {
-      const int blk = wave + kWaves * i;
-      const int tok0 = blk * kBlockTokens;
-      // ---- S^T = K Q^T for the two 16-row tiles; tile e row r is token (r/4)*8 + e*4 + r%4
-      floatx4 s[2];
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        s[e] = floatx4{0.f, 0.f, 0.f, 0.f};
-        const int t = ((r16 >> 2) << 3) + e * 4 + (r16 & 3);
-        const unsigned char* rowp = k_lds + t * G_::kRowBytes;
-        const int key = key_k(t);
-        if (FP8) {
-#pragma unroll
-          for (int p = 0; p < G_::kChunks / 4; ++p) {
-            const int c = ((p * 4 + q4) ^ key) & (G_::kChunks - 1);
-            const uint4 raw = *(const uint4*)(rowp + c * 16);
-            s[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fp8x8_to_bf16(raw.x, raw.y), qop[2 * p], s[e], 0, 0, 0);
-            s[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fp8x8_to_bf16(raw.z, raw.w), qop[2 * p + 1], s[e], 0, 0, 0);
-          }
-        } else {
-#pragma unroll
-          for (int kk = 0; kk < G_::kKK; ++kk) {
-            const int c = ((kk * 4 + q4) ^ key) & (G_::kChunks - 1);
-            const bf16x8 kop = *(const bf16x8*)(rowp + c * 16);
-            s[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[kk], s[e], 0, 0, 0);
-          }
+        for (int kk = 0; kk < G_::kKK; ++kk) {
+          const int c = ((kk * 4 + q4) ^ key) & (G_::kChunks - 1);
+          const bf16x8 kop = *(const bf16x8*)(rowp + c * 16);
+          s[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop, qop[kk], s[e], 0, 0, 0);
         }
       }
-      // This lane now holds, for head r16, the scores of tokens tok0 + q4*8 + (0..7):
-      // s[0][i] -> +i, s[1][i] -> +4+i.
-      const float sc = FP8 ? a.scale_log2 * ksc[stage] : a.scale_log2;
-      const float vs = FP8 ? vsc[stage] : 1.f;
-      float x[8];
-      const int tbase = tok0 + q4 * 8;
+    }
+    // This lane now holds, for head r16, the scores of tokens tok0 + q4*8 + (0..7):
+    // s[0][i] -> +i, s[1][i] -> +4+i.
+    const float sc = FP8 ? a.scale_log2 * kscale : a.scale_log2;
+    const float vs = FP8 ? vscale : 1.f;
+    float x[8];
+    const int tbase = tok0 + q4 * 8;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float raw = (j < 4) ? s[0][j] : s[1][j - 4];
-        x[j] = (tbase + j < len) ? raw * sc : -INFINITY;
-      }
-      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-      mx = xor32_max(xor16_max(mx));
-      const float m_new = fmaxf(m_run, mx);       // finite from the first block on: token 0 is always live
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      float psum = 0.f;
-      bf16x8 pop;
+    for (int j = 0; j < 8; ++j) {
+      const float raw = (j < 4) ? s[0][j] : s[1][j - 4];
+      x[j] = (tbase + j < len) ? raw * sc : -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = xor32_max(xor16_max(mx));
+    const float m_new = fmaxf(m_run, mx);       // finite: the first token of a block is always live
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    float psum = 0.f;
+    bf16x8 pop;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float p = __builtin_amdgcn_exp2f(x[j] - m_new);
-        psum += p;
-        pop[j] = (__bf16)(FP8 ? p * vs : p);
-      }
-      l_run = l_run * alpha + psum;
-      if (__builtin_amdgcn_ballot_w64(m_new > m_run)) {
+    for (int j = 0; j < 8; ++j) {
+      const float p = __builtin_amdgcn_exp2f(x[j] - m_new);
+      psum += p;
+      pop[j] = (__bf16)(FP8 ? p * vs : p);
+    }
+    l_run = l_run * alpha + psum;
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run)) {
 #pragma unroll
-        for (int dt = 0; dt < G_::kDT; ++dt) acc[dt] *= alpha;
-      }
-      m_run = m_new;
-      // ---- O^T += V^T P^T : A = V^T tile (16 dims x 32 tokens) read transposed from LDS
+      for (int dt = 0; dt < G_::kDT; ++dt) acc[dt] *= alpha;
+    }
+    m_run = m_new;
+    // ---- O^T += V^T P^T : A = V^T tile (16 dims x 32 tokens) read transposed from LDS
 #pragma unroll
-      for (int dt = 0; dt < G_::kDT; ++dt) {
-        bf16x8 vop;
-        if (FP8) {
-          typedef __attribute__((address_space(3))) intx2 lds_i2;
-          const int t = q4 * 8 + (r16 >> 1);
-          const int c = (dt ^ key_v8(t)) & (G_::kChunks - 1);
-          const intx2 raw = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-              (lds_i2*)(v_lds + t * G_::kRowBytes + c * 16 + (r16 & 1) * 8));
-          vop = fp8x8_to_bf16((uint32_t)raw[0], (uint32_t)raw[1]);
-        } else {
-          typedef __attribute__((address_space(3))) shortx4 lds_s4;
+    for (int dt = 0; dt < G_::kDT; ++dt) {
+      bf16x8 vop;
+      if (FP8) {
+        typedef __attribute__((address_space(3))) intx2 lds_i2;
+        const int t = q4 * 8 + (r16 >> 1);
+        const int c = (dt ^ key_v8(t)) & (G_::kChunks - 1);
+        const intx2 raw = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+            (lds_i2*)(v_lds + t * G_::kRowBytes + c * 16 + (r16 & 1) * 8));
+        vop = fp8x8_to_bf16((uint32_t)raw[0], (uint32_t)raw[1]);
+      } else {
+        typedef __attribute__((address_space(3))) shortx4 lds_s4;
 #pragma unroll
-          for (int hf = 0; hf < 2; ++hf) {
-            const int t = q4 * 8 + hf * 4 + (r16 >> 2);
-            const int c = ((dt * 2 + ((r16 & 3) >> 1)) ^ key_v16(t)) & (G_::kChunks - 1);
-            const shortx4 raw = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_s4*)(v_lds + t * G_::kRowBytes + c * 16 + (r16 & 1) * 8));
-            const bf16x4 h4 = __builtin_bit_cast(bf16x4, raw);
-            vop[hf * 4 + 0] = h4[0]; vop[hf * 4 + 1] = h4[1]; vop[hf * 4 + 2] = h4[2]; vop[hf * 4 + 3] = h4[3];
-          }
+        for (int hf = 0; hf < 2; ++hf) {
+          const int t = q4 * 8 + hf * 4 + (r16 >> 2);
+          const int c = ((dt * 2 + ((r16 & 3) >> 1)) ^ key_v16(t)) & (G_::kChunks - 1);
+          const shortx4 raw = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s4*)(v_lds + t * G_::kRowBytes + c * 16 + (r16 & 1) * 8));
+          const bf16x4 h4 = __builtin_bit_cast(bf16x4, raw);
+          vop[hf * 4 + 0] = h4[0]; vop[hf * 4 + 1] = h4[1]; vop[hf * 4 + 2] = h4[2]; vop[hf * 4 + 3] = h4[3];
         }
-        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop, acc[dt], 0, 0, 0);
       }
-    };
+      acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, pop, acc[dt], 0, 0, 0);
+    }
+  };
 
-    // ---- software pipeline over this wave's blocks
-    if (my_blocks > 0) refill_pages(0);
+  // ---- software pipeline over this worker's run of n_mine blocks
+#pragma unroll
+  for (int st = 0; st < G_::kStages; ++st) {
+    if (st < n_mine) issue(st);
+  }
+  for (int i0 = 0; i0 < n_mine; i0 += G_::kStages) {
 #pragma unroll
     for (int st = 0; st < G_::kStages; ++st) {
-      if (st < my_blocks) issue(st, st);
-    }
-    for (int i0 = 0; i0 < my_blocks; i0 += G_::kStages) {
-#pragma unroll
-      for (int st = 0; st < G_::kStages; ++st) {
-        const int i = i0 + st;
-        if (i < my_blocks) {
-          commit(st);
-          const int nxt = i + G_::kStages;
-          compute(st, i);
-          // the page-id window covers local blocks [32k, 32k + 32); the loads of block `nxt` are the
-          // first to need the next window and nothing issued earlier looks at the old one again.
-          if (nxt < my_blocks) {
-            if ((nxt & 31) == 0) refill_pages(nxt);
-            issue(st, nxt);
-          }
-        }
+      const int i = i0 + st;
+      if (i < n_mine) {
+        commit(st);
+        const float kscale = FP8 ? ksc[st] : 1.f, vscale = FP8 ? vsc[st] : 1.f;
+        if (i + G_::kStages < n_mine) issue(st);   // the registers just drained take the next block
+        if (i == 0 || cc.blk == 0) begin_segment();
+        compute(kscale, vscale);
+        if (cc.blk == cc.n - 1 || i == n_mine - 1) end_segment();
+        if (i + 1 < n_mine) advance(cc);
       }
     }
-
-    // ---- merge the four waves through LDS
-    l_run = xor32_add(xor16_add(l_run));
-    {
-      float* my = (float*)lds[wave];
-#pragma unroll
-      for (int dt = 0; dt < G_::kDT; ++dt) *(floatx4*)(my + r16 * D + dt * 16 + q4 * 4) = acc[dt];
-      if (q4 == 0) {
-        ml_s[wave][r16][0] = m_run;
-        ml_s[wave][r16][1] = l_run;
-      }
-    }
-    __syncthreads();
-    {
-      constexpr int kPer = D / 16;             // output elements per thread
-      const int n = tid >> 4;                  // head within the group tile
-      const int d0 = (tid & 15) * kPer;
-      float mw[kWaves], mmax = -INFINITY;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        mw[w] = ml_s[w][n][0];
-        mmax = fmaxf(mmax, mw[w]);
-      }
-      float o[kPer];
-#pragma unroll
-      for (int e = 0; e < kPer; ++e) o[e] = 0.f;
-      float lsum = 0.f;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        const float f = (mw[w] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw[w] - mmax);
-        lsum += f * ml_s[w][n][1];
-        const float* src = (const float*)lds[w] + n * D + d0;
-#pragma unroll
-        for (int e = 0; e < kPer; ++e) o[e] += f * src[e];
-      }
-      if (h0 + n < group) {
-        if (n_pieces == 1) {
-          const float inv = 1.f / lsum;
-          __bf16* dst = (__bf16*)a.out + ((size_t)b * a.hq + (size_t)g * group + h0 + n) * D + d0;
-#pragma unroll
-          for (int e = 0; e < kPer; e += 2) {
-            bf16x2 pr;
-            pr[0] = (__bf16)(o[e] * inv);
-            pr[1] = (__bf16)(o[e + 1] * inv);
-            *(bf16x2*)(dst + e) = pr;
-          }
-        } else {
-          const size_t slot = (size_t)piece * hkv + g;
-          float* dst = a.partial_o + (slot * group + h0 + n) * D + d0;
-#pragma unroll
-          for (int e = 0; e < kPer; ++e) dst[e] = o[e];
-          if ((tid & 15) == 0) {
-            a.partial_ml[(slot * group + h0 + n) * 2 + 0] = mmax;
-            a.partial_ml[(slot * group + h0 + n) * 2 + 1] = lsum;
-          }
-        }
-      }
-    }
-    __syncthreads();   // tiles and item_s are free again
   }
 }
 

@@ -9,11 +9,7 @@ namespace {
 
 constexpr int kPlanThreads = 1024;
 
-__device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
+constexpr int kLdsPrefix = 8192;   // batches up to this size keep the scan in LDS for the searches
 
 // Exclusive scan of one int per thread across the workgroup; returns this thread's prefix
 // and leaves the workgroup total in *total.
@@ -36,70 +32,61 @@ __device__ int block_exclusive_scan(int v, int* wave_tot /*[16]*/, int* total) {
   return base + incl - v;
 }
 
-// Decode partition: pieces of C tokens, C the smallest kMinChunk << k (k <= kMaxDoublings)
-// whose piece count fits `cap`, else one piece per trajectory (C = 0).
+// Decode partition.  Every trajectory is cut into blocks of kBlockTokens tokens; the rows
+// (trajectory b, row r in [0, rows_per_b)) are laid end to end, b outermost, each with
+// n_b = ceil(L_b / kBlockTokens) blocks; the resulting sequence of T blocks is dealt to the W
+// workers in equal contiguous runs of per = ceil(T / W) blocks.  Written out: the exclusive
+// scan of n_b, the run length, T, and for every worker the (b, r, block) its run starts at.
 __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
-    const int32_t* __restrict__ ctx_lens, int32_t batch, int32_t cap, int32_t* __restrict__ header,
-    int32_t* __restrict__ item_b, int32_t* __restrict__ item_start, int32_t* __restrict__ row_first) {
-  __shared__ int sums[kMaxDoublings + 1];
+    const int32_t* __restrict__ ctx_lens, int32_t batch, int32_t rows_per_b, int32_t workers,
+    int32_t* __restrict__ header, int32_t* __restrict__ prefix, int32_t* __restrict__ wstart) {
   __shared__ int wave_tot[kPlanThreads / 64];
-  __shared__ int chunk_s;
+  __shared__ int prefix_s[kLdsPrefix + 1];
   const int tid = threadIdx.x;
-  if (tid <= kMaxDoublings) sums[tid] = 0;
-  __syncthreads();
-  int local[kMaxDoublings + 1];
-#pragma unroll
-  for (int k = 0; k <= kMaxDoublings; ++k) local[k] = 0;
-  for (int b = tid; b < batch; b += kPlanThreads) {
-    const int len = ctx_lens[b];
-#pragma unroll
-    for (int k = 0; k <= kMaxDoublings; ++k) {
-      const int c = kMinChunk << k;
-      local[k] += (len + c - 1) / c;
-    }
-  }
-#pragma unroll
-  for (int k = 0; k <= kMaxDoublings; ++k) {
-    const int s = wave_sum(local[k]);
-    if ((tid & 63) == 0 && s) atomicAdd(&sums[k], s);
-  }
-  __syncthreads();
-  if (tid == 0) {
-    int chosen = 0;
-    for (int k = 0; k <= kMaxDoublings; ++k) {
-      if (sums[k] <= cap) {
-        chosen = kMinChunk << k;
-        break;
-      }
-    }
-    chunk_s = chosen;
-  }
-  __syncthreads();
-  const int chunk = chunk_s;
+  const bool in_lds = batch <= kLdsPrefix;
   int running = 0;
   for (int b0 = 0; b0 < batch; b0 += kPlanThreads) {
     const int b = b0 + tid;
-    int len = 0, count = 0;
-    if (b < batch) {
-      len = ctx_lens[b];
-      count = chunk ? (len + chunk - 1) / chunk : (len > 0 ? 1 : 0);
-    }
+    const int count = (b < batch) ? (ctx_lens[b] + kBlockTokens - 1) / kBlockTokens : 0;
     int tile_total;
     const int first = running + block_exclusive_scan(count, wave_tot, &tile_total);
     if (b < batch) {
-      row_first[b] = first;
-      for (int s = 0; s < count; ++s) {
-        item_b[first + s] = b;
-        item_start[first + s] = s * chunk;
-      }
+      prefix[b] = first;
+      if (in_lds) prefix_s[b] = first;
     }
     running += tile_total;
   }
   if (tid == 0) {
-    row_first[batch] = running;
-    header[kPlanChunk] = chunk;
-    header[kPlanItems] = running;
-    header[kPlanCounter] = 0;
+    prefix[batch] = running;
+    if (in_lds) prefix_s[batch] = running;
+  }
+  const int total = running * rows_per_b;
+  const int per = max(1, (total + workers - 1) / workers);
+  if (tid == 0) {
+    header[kPlanPer] = per;
+    header[kPlanTotal] = total;
+    header[kPlanWorkers] = workers;
+    header[kPlanRowsPerB] = rows_per_b;
+  }
+  __threadfence_block();
+  __syncthreads();   // prefix[] written above is read below by other threads of this workgroup
+  for (int w = tid; w < workers; w += kPlanThreads) {
+    const long x = (long)w * per;
+    int4 st = make_int4(-1, -1, -1, 0);
+    if (x < total) {
+      // largest b with rows_per_b * prefix[b] <= x (rows without blocks can never be the answer
+      // because the next row then starts at the same position)
+      const int* pf = in_lds ? prefix_s : prefix;
+      int lo = 0, hi = batch;
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((long)rows_per_b * pf[mid] <= x) lo = mid; else hi = mid;
+      }
+      const int n = pf[lo + 1] - pf[lo];
+      const int rem = (int)(x - (long)rows_per_b * pf[lo]);
+      st = make_int4(lo, rem / n, rem % n, n);
+    }
+    *(int4*)(wstart + 4 * w) = st;
   }
 }
 
@@ -124,18 +111,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
     }
     running += tile_total;
   }
-  if (tid == 0) {
-    header[kPlanTiles] = running < cap ? running : cap;
-    header[kPlanCounter] = 0;
-  }
+  if (tid == 0) header[kPlanTiles] = running < cap ? running : cap;
 }
 
 }  // namespace
 
-hipError_t launch_plan_decode(const int32_t* ctx_lens, int32_t batch, int32_t cap, int32_t* header,
-                              int32_t* item_b, int32_t* item_start, int32_t* row_first, hipStream_t s) {
-  hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(kPlanThreads), 0, s, ctx_lens, batch, cap, header,
-                     item_b, item_start, row_first);
+hipError_t launch_plan_decode(const int32_t* ctx_lens, int32_t batch, int32_t rows_per_b, int32_t workers,
+                              int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s) {
+  hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(kPlanThreads), 0, s, ctx_lens, batch, rows_per_b, workers,
+                     header, prefix, wstart);
   return hipGetLastError();
 }
 

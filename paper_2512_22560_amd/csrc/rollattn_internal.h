@@ -10,24 +10,28 @@
 namespace rollattn {
 
 constexpr int kPageSize = 16;
-constexpr int kNumCUs = 256;          // MI355X
-constexpr int kItemBudget = 16384;    // target upper bound on (piece, kv head) work items per decode call
-constexpr int kMinChunk = 256;        // smallest KV piece, tokens
-constexpr int kMaxDoublings = 8;      // largest piece = kMinChunk << kMaxDoublings before "one piece per row"
-constexpr int kAppendTileRows = 256;  // query rows (token, head-in-group pairs) per append workgroup
+constexpr int kNumCUs = 256;            // MI355X
+constexpr int kBlockTokens = 32;        // unit of the decode partition: two pages
+constexpr int kMfmaDecodeWgs = 2 * kNumCUs;   // 4 wave-workers each
+constexpr int kMfmaHeadTile = 16;       // query heads per MFMA decode row
+constexpr int kF32DecodeWgs = 4 * kNumCUs;    // one workgroup-worker each
+constexpr int kF32HeadTile = 4;         // query heads per float32 decode row
+constexpr int kAppendTileRows = 256;    // query rows (token, head-in-group pairs) per append workgroup
 
 // Header words of the plan, at the start of the workspace.
-enum PlanWord { kPlanChunk = 0, kPlanItems = 1, kPlanCounter = 2, kPlanTiles = 3, kPlanWords = 64 };
+enum PlanWord { kPlanPer = 0, kPlanTotal = 1, kPlanWorkers = 2, kPlanRowsPerB = 3, kPlanTiles = 4, kPlanWords = 64 };
 
 // Byte offsets of the workspace regions (all multiples of 256).
 struct WorkspaceLayout {
-  int32_t cap;            // capacity in pieces (decode) or query tiles (append)
+  int32_t workers;        // decode: number of workers W; append: capacity in query tiles
+  int32_t head_tile;      // decode: query heads per row (16 or 4)
+  int32_t rows_per_b;     // decode: rows per trajectory = Hkv * ceil(G / head_tile)
   size_t header;          // int32[kPlanWords]
-  size_t item_b;          // int32[cap]   trajectory of a piece / tile
-  size_t item_start;      // int32[cap]   first token of a piece / first chunk row of a tile
-  size_t row_first;       // int32[B + 1] first piece of every trajectory (exclusive scan)
-  size_t partial_ml;      // float[cap * Hkv][G][2]   (max in log2 units, sum)
-  size_t partial_o;       // float[cap * Hkv][G][D]   un-normalised
+  size_t prefix;          // decode: int32[B + 1] exclusive scan of per-trajectory block counts
+  size_t wstart;          // decode: int32[W][4] first (b, row, block) of every worker; append: tile list
+  size_t tile_q0;         // append: int32[cap]
+  size_t partial_ml;      // float[2 W][head_tile][2]   (max in log2 units, sum)
+  size_t partial_o;       // float[2 W][head_tile][D]   un-normalised
   size_t total;
 };
 
@@ -44,13 +48,12 @@ struct DecodeArgs {
   void* out;
   const float* k_scale;
   const float* v_scale;
-  int32_t* header;
-  const int32_t* item_b;
-  const int32_t* item_start;
-  const int32_t* row_first;
+  const int32_t* header;
+  const int32_t* prefix;
+  const int32_t* wstart;
   float* partial_ml;
   float* partial_o;
-  int32_t batch, hq, hkv, group, max_pages;
+  int32_t batch, hq, hkv, group, max_pages, head_tile, rows_per_b;
   float scale_log2;     // sm_scale * log2(e)
 };
 
@@ -73,8 +76,8 @@ struct AppendArgs {
 };
 
 // Launchers (defined in the .hip files).  Each returns the hipError_t of its launch.
-hipError_t launch_plan_decode(const int32_t* ctx_lens, int32_t batch, int32_t cap, int32_t* header,
-                              int32_t* item_b, int32_t* item_start, int32_t* row_first, hipStream_t s);
+hipError_t launch_plan_decode(const int32_t* ctx_lens, int32_t batch, int32_t rows_per_b, int32_t workers,
+                              int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s);
 hipError_t launch_plan_append(const int32_t* q_lens, int32_t batch, int32_t tile_tokens, int32_t cap,
                               int32_t* header, int32_t* tile_b, int32_t* tile_q0, hipStream_t s);
 hipError_t launch_decode_f32(const DecodeArgs& a, int head_dim, int grid, hipStream_t s);

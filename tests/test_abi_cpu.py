@@ -59,18 +59,25 @@ def test_descriptor_errors_are_reported_before_any_launch():
     assert lib.rollattn_profile_read(None, 0) == 0
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", range(8))
 def test_host_plan_twin_matches_the_oracle_rule(seed):
     rng = np.random.default_rng(seed)
     hkv = int(rng.choice([1, 2, 4, 8]))
-    batch = int(rng.choice([1, 3, 64, 700, 5000]))
-    hi = int(rng.choice([40, 3000, 70000]))
+    group = int(rng.choice([1, 4, 5, 16, 20]))
+    f32 = bool(seed % 2)
+    batch = int(rng.choice([1, 3, 64, 700]))
+    hi = int(rng.choice([40, 3000, 20000]))
     lens = rng.integers(0, hi, batch).astype(np.int32)
-    d = _desc(batch=batch, num_kv_heads=hkv, num_q_heads=hkv * 4, max_pages_per_seq=hi // 16 + 1)
-    chunk, items = B.debug_plan(d, lens)
-    ref_chunk, ref_items, _ = O.split_plan(lens, hkv)
-    assert chunk == ref_chunk
-    assert np.array_equal(items, ref_items)
+    d = _desc(batch=batch, num_kv_heads=hkv, num_q_heads=hkv * group, max_pages_per_seq=hi // 16 + 1,
+              head_dim=128, q_dtype=B.F32 if f32 else B.BF16, kv_dtype=B.F32 if f32 else B.BF16)
+    tile = 4 if f32 else 16
+    rows_per_b = hkv * -(-group // tile)
+    workers = B.plan_workers(d)
+    assert workers == (1024 if f32 else 2048)
+    per, total, segs = B.debug_plan(d, lens)
+    o_per, o_total, _, o_segs = O.split_plan(lens, rows_per_b, workers)
+    assert (per, total) == (o_per, o_total)
+    assert np.array_equal(segs, o_segs)
 
 
 def test_plan_on_the_benchmark_length_draws():
@@ -80,7 +87,7 @@ def test_plan_on_the_benchmark_length_draws():
         lens, _, table, npages = W.draw_structure(w)
         d = _desc(batch=w.batch, num_kv_heads=w.num_kv_heads, num_q_heads=w.num_q_heads, head_dim=128,
                   max_pages_per_seq=table.shape[1], num_pages=npages, q_dtype=B.BF16, kv_dtype=B.BF16)
-        chunk, items = B.debug_plan(d, lens)
-        ref_chunk, ref_items, _ = O.split_plan(lens, w.num_kv_heads)
-        assert chunk == ref_chunk and np.array_equal(items, ref_items)
-        assert items[:, 2].sum() == lens.sum()
+        per, total, segs = B.debug_plan(d, lens)
+        o_per, o_total, _, o_segs = O.split_plan(lens, w.num_kv_heads, 2048)
+        assert (per, total) == (o_per, o_total) and np.array_equal(segs, o_segs)
+        assert segs[:, 4].sum() == total == w.num_kv_heads * ((lens + 31) // 32).sum()

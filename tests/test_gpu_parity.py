@@ -69,10 +69,11 @@ def test_decode_edge_lengths(qd, kvd):
     assert not out[0].any() and not out[20].any()          # empty contexts give zero rows
 
 
-def test_decode_long_pieces_cross_the_page_id_window():
-    # Many KV heads shrink the piece budget, long rows then force 8192-token pieces: every wave walks
-    # 64 blocks and has to refill its window of page ids.  Logical pages alias a small physical pool
-    # (as shared prefixes do), which keeps the pool small; the oracle reads through the same table.
+def test_decode_long_runs_cross_the_page_id_window():
+    # 20 rows x 64 KV heads x ~1700 blocks over 2048 workers: every wave walks ~1000 blocks, crossing
+    # rows and refilling its 32-block window of page ids many times.  Logical pages alias a small
+    # physical pool (as shared prefixes do), which keeps the pool small; the oracle reads through the
+    # same table.
     rng = np.random.default_rng(103)
     batch, hkv, d, n_phys = 20, 64, 64, 96
     lens = rng.integers(52000, 56000, batch)
@@ -90,11 +91,11 @@ def test_decode_long_pieces_cross_the_page_id_window():
     desc = B.make_desc(q, kp, pt, sm_scale=0.125)
     ws = B.alloc_workspace(desc, batch, DEV)
     out = B.attn_decode(q, kp, vp, pt, cl, sm_scale=0.125, workspace=ws)
-    chunk, items = B.read_plan(desc, ws, cl)
-    assert chunk == 8192
+    per, total, _ = B.read_plan(desc, ws)
+    assert per > 64          # every wave refills its 32-block window of page ids at least twice
     ref = O.attn_decode(W.raw_numpy(q), W.raw_numpy(kp), W.raw_numpy(vp), table, lens, sm_scale=0.125,
                         q_dtype="bf16", kv_dtype="bf16")
-    check(out, ref, "bf16", "8192-token pieces")
+    check(out, ref, "bf16", "long runs")
 
 
 def test_single_key_returns_value_exactly_and_fp8_codes_decode_exactly():
@@ -161,13 +162,14 @@ def test_debug_gather_is_byte_exact(kvd):
             assert got.tobytes() == np.ascontiguousarray(ref).tobytes()
 
 
-@pytest.mark.parametrize("seed,batch,hi", [(1, 64, 8192), (2, 5, 300), (3, 3000, 2000), (4, 300, 40000)])
-def test_device_plan_equals_host_twin_and_oracle_rule(seed, batch, hi):
+@pytest.mark.parametrize("seed,batch,hi,group", [(1, 64, 8192, 4), (2, 5, 300, 1), (3, 3000, 2000, 20), (4, 300, 40000, 16),
+                                                 (5, 9000, 100, 2)])
+def test_device_plan_equals_host_twin_and_oracle_rule(seed, batch, hi, group):
     rng = np.random.default_rng(seed)
     lens = rng.integers(0, hi, batch).astype(np.int32)
     hkv, d = 2, 64
     max_pages = hi // 16 + 1
-    q = torch.zeros((batch, 4, d), dtype=torch.bfloat16, device=DEV)
+    q = torch.zeros((batch, hkv * group, d), dtype=torch.bfloat16, device=DEV)
     # every row points at page 0: the plan must not depend on page ids, and the pool stays tiny
     kp = torch.zeros((1, hkv, 16, d), dtype=torch.bfloat16, device=DEV)
     pt = torch.zeros((batch, max_pages), dtype=torch.int32, device=DEV)
@@ -175,11 +177,13 @@ def test_device_plan_equals_host_twin_and_oracle_rule(seed, batch, hi):
     desc = B.make_desc(q, kp, pt, sm_scale=1.0)
     ws = B.alloc_workspace(desc, batch, DEV)
     B.attn_decode(q, kp, kp, pt, cl, sm_scale=1.0, workspace=ws)
-    chunk, items = B.read_plan(desc, ws, cl)
-    h_chunk, h_items = B.debug_plan(desc, lens)
-    o_chunk, o_items, _ = O.split_plan(lens, hkv)
-    assert chunk == h_chunk == o_chunk
-    assert np.array_equal(items, h_items) and np.array_equal(items, o_items)
+    per, total, starts = B.read_plan(desc, ws)
+    h_per, h_total, h_segs = B.debug_plan(desc, lens)
+    rows_per_b = hkv * -(-group // 16)
+    o_per, o_total, o_starts, o_segs = O.split_plan(lens, rows_per_b, B.plan_workers(desc))
+    assert (per, total) == (h_per, h_total) == (o_per, o_total)
+    assert np.array_equal(starts, o_starts)
+    assert np.array_equal(h_segs, o_segs)
 
 
 # ------------------------------------------------------------------ append

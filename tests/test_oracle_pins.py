@@ -357,20 +357,30 @@ def test_split_then_combine_equals_unsplit(chunk):
             np.testing.assert_allclose(O.combine_partials(ms, ls, os_), whole[bb, h], atol=1e-12)
 
 
-def test_split_plan_covers_each_context_once_and_respects_the_cap():
+def test_split_plan_covers_every_block_once_in_equal_runs():
     rng = np.random.default_rng(5)
-    for hkv, lens in ((8, rng.integers(0, 40000, 300)), (4, rng.integers(1, 300, 10)), (8, np.array([0, 0])),
-                      (2, rng.integers(60000, 70000, 9000))):
-        c, items, counts = O.split_plan(lens, hkv)
-        cap = max(len(lens), 16384 // hkv)
-        assert len(items) <= cap and counts.sum() == len(items)
-        assert c == 0 or (c >= 256 and (c & (c - 1)) == 0)
-        pos = {}
-        for b, start, length, s in items.tolist():
-            assert length > 0 and start == pos.get(b, 0) and (c == 0 or length <= c)
-            assert s == (0 if b not in pos else s) and (c == 0 or s == start // c)
-            pos[b] = start + length
-        for b, L in enumerate(lens.tolist()):
-            assert pos.get(b, 0) == L
-        if c > 256:   # the next smaller chunk would have overflowed the cap
-            assert int(((lens + c // 2 - 1) // (c // 2)).sum()) > cap
+    for rows_per_b, workers, lens in ((8, 64, rng.integers(0, 4000, 30)), (4, 2048, rng.integers(1, 300, 10)),
+                                      (8, 16, np.array([0, 0])), (2, 7, rng.integers(0, 90, 50)),
+                                      (1, 5, np.array([0, 33, 0, 0, 1, 64, 0]))):
+        per, total, starts, segs = O.split_plan(lens, rows_per_b, workers)
+        n_blocks = (lens + 31) // 32
+        assert total == rows_per_b * n_blocks.sum() and per == max(1, -(-total // workers))
+        seen = {}
+        by_worker = {}
+        for w, b, r, k, cnt, slot in segs.tolist():
+            assert cnt > 0 and k + cnt <= n_blocks[b]
+            for kk in range(k, k + cnt):
+                assert (b, r, kk) not in seen
+                seen[(b, r, kk)] = w
+            by_worker.setdefault(w, []).append((b, r, k, cnt, slot))
+        assert len(seen) == total                                   # every block exactly once
+        for w, pieces in by_worker.items():
+            assert sum(p[3] for p in pieces) == min(per, total - w * per)   # equal runs
+            assert tuple(starts[w][:3]) == pieces[0][:3]
+            for i, (b, r, k, cnt, slot) in enumerate(pieces):
+                whole = k == 0 and cnt == n_blocks[b]
+                assert slot == (-1 if whole else (0 if i == 0 else 1))
+                if 0 < i < len(pieces) - 1:
+                    assert whole                                    # only the ends of a run can be partial
+        assert sorted(by_worker) == list(range(len(by_worker)))     # workers are used in order
+        assert all(starts[w][0] == -1 for w in range(len(by_worker), workers))

@@ -141,8 +141,8 @@ int32_t rollattn_plan_capacity(const rollattn_desc *desc);
 int32_t rollattn_plan_workers(const rollattn_desc *desc);
 
 /* Copies the plan the last attn_decode call left in `workspace` back to the host
- * (synchronises the stream): per, T, and 4 int32 per worker, (b, r, block, blocks in that
- * row) of the first block of its run, or (-1, -1, -1, 0) for a worker without blocks.
+ * (synchronises the stream): per, T, and 4 int32 per worker, (b, r << 20 | block, L_b, blocks
+ * in its run) for the first block of its run, or (-1, 0, 0, 0) for a worker without blocks.
  * starts_out must hold 4 * rollattn_plan_workers(desc) int32. */
 int rollattn_debug_read_plan(const rollattn_desc *desc, const void *workspace, int32_t *per_out,
                              int32_t *total_out, int32_t *starts_out, void *hip_stream);

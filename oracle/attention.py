@@ -208,8 +208,8 @@ def split_plan(ctx_lens, rows_per_b, workers, block_tokens=32):
     (b, r), r in [0, rows_per_b), are laid end to end with b outermost, n_b blocks each; the
     resulting sequence of T blocks is dealt to the workers in equal contiguous runs of
     per = max(1, ceil(T / workers)) blocks.  Returns (per, T, starts, segments): starts is
-    int32 [workers, 4] with the (b, r, block, n_b) each run begins at (-1, -1, -1, 0 for
-    workers without blocks); segments is int32 [n, 6] with one line per maximal piece of a row
+    int32 [workers, 4] with (b, r << 20 | block, L_b, blocks in the run) for the block each run
+    begins at ((-1, 0, 0, 0) for workers without blocks); segments is int32 [n, 6] with one line per maximal piece of a row
     inside one run, in worker order: (worker, b, r, first block, block count, slot) where slot
     is -1 if the piece is the whole row, else 0 if it is the first piece of the run, else 1."""
     lens = np.asarray(ctx_lens, dtype=np.int64)
@@ -220,14 +220,14 @@ def split_plan(ctx_lens, rows_per_b, workers, block_tokens=32):
     total = len(seq)
     per = max(1, -(-total // workers))
     starts = np.zeros((workers, 4), dtype=np.int32)
-    starts[:, :3] = -1
+    starts[:, 0] = -1
     segments = []
     for w in range(workers):
         run = seq[w * per:(w + 1) * per]
         if not run:
             continue
         b, r, k = run[0]
-        starts[w] = (b, r, k, n_blocks[b])
+        starts[w] = (b, (r << 20) | k, lens[b], len(run))
         pieces = []
         for (b, r, k) in run:
             if pieces and pieces[-1][0] == b and pieces[-1][1] == r:

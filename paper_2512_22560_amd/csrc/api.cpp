@@ -247,6 +247,8 @@ int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, c
   if (workspace_bytes < w.total) return ROLLATTN_EWORKSPACE;
   // the block sequence is indexed with 32-bit integers
   if ((int64_t)desc->batch * w.rows_per_b * ((int64_t)desc->max_pages_per_seq / 2 + 1) > INT32_MAX) return ROLLATTN_ESHAPE;
+  // a worker's start record packs the row index into 11 bits and the block index into 20
+  if (w.rows_per_b > 2047 || desc->max_pages_per_seq / 2 + 1 > (1 << 20)) return ROLLATTN_ESHAPE;
 
   hipStream_t s = (hipStream_t)hip_stream;
   char* base = (char*)workspace;

@@ -111,12 +111,10 @@ __global__ __launch_bounds__(kThreads) void decode_f32_kernel(const DecodeArgs a
   const int group = a.group, hkv = a.hkv, rows_per_b = a.rows_per_b;
   const int n_ht = rows_per_b / hkv;
   const int worker = blockIdx.x;
-  const int per = a.header[kPlanPer];
-  const int total = a.header[kPlanTotal];
-  if ((long)worker * per >= total) return;
-  int left = min(per, total - worker * per);
-  const int4 st = *(const int4*)(a.wstart + 4 * worker);
-  int b = st.x, r = st.y, blk = st.z, n = st.w;
+  const int4 st = *(const int4*)(a.wstart + 4 * worker);   // (b, r << 20 | block, L_b, run length)
+  if (st.x < 0) return;
+  int left = st.w;
+  int b = st.x, r = st.y >> 20, blk = st.y & 0xFFFFF, n = (st.z + kBlockTokens - 1) / kBlockTokens;
   bool first_segment = true;
   while (left > 0) {
     const int cnt = min(left, n - blk);                 // blocks of this row that are ours

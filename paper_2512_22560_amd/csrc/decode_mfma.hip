@@ -98,23 +98,19 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const DecodeAr
   unsigned char* const v_lds = lds[wave] + G_::kTileBytes;
 
   const int worker = blockIdx.x * kWaves + wave;
-  const int per = a.header[kPlanPer];
-  const int total = a.header[kPlanTotal];
-  if ((long)worker * per >= total) return;
-  const int n_mine = min(per, total - worker * per);
+  const int4 start = *(const int4*)(a.wstart + 4 * worker);   // (b, r << 20 | block, L_b, run length)
+  if (start.x < 0) return;
+  const int n_mine = __builtin_amdgcn_readfirstlane(start.w);
   const int group = a.group, hkv = a.hkv, rows_per_b = a.rows_per_b;
   const int n_ht = rows_per_b / hkv;
   const size_t tile_stride = (size_t)kPageSize * G_::kRowBytes;   // bytes of one (page, head) tile
 
   Cursor pc;   // producer: next block to request from HBM
-  {
-    const int4 st = *(const int4*)(a.wstart + 4 * worker);
-    pc.b = __builtin_amdgcn_readfirstlane(st.x);
-    pc.r = __builtin_amdgcn_readfirstlane(st.y);
-    pc.blk = __builtin_amdgcn_readfirstlane(st.z);
-    pc.n = __builtin_amdgcn_readfirstlane(st.w);
-    pc.len = a.ctx_lens[pc.b];
-  }
+  pc.b = __builtin_amdgcn_readfirstlane(start.x);
+  pc.r = __builtin_amdgcn_readfirstlane(start.y) >> 20;
+  pc.blk = __builtin_amdgcn_readfirstlane(start.y) & 0xFFFFF;
+  pc.len = __builtin_amdgcn_readfirstlane(start.z);
+  pc.n = (pc.len + kBlockTokens - 1) / kBlockTokens;
   Cursor cc = pc;   // consumer: block being computed
   auto advance = [&](Cursor& c) {
     if (++c.blk < c.n) return;
@@ -123,9 +119,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const DecodeAr
     c.r = 0;
     do {
       ++c.b;
-      c.n = a.prefix[c.b + 1] - a.prefix[c.b];
-    } while (c.n == 0);
-    c.len = a.ctx_lens[c.b];
+      c.len = a.ctx_lens[c.b];
+    } while (c.len == 0);
+    c.n = (c.len + kBlockTokens - 1) / kBlockTokens;
   };
 
   // ---- producer state: a window of 64 page ids (32 blocks) of the current row, one per lane
@@ -154,20 +150,34 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const DecodeAr
       ksc[stage] = a.k_scale[pid];
       vsc[stage] = a.v_scale[pid];
     }
+    const unsigned char* kt0 = (const unsigned char*)a.k_pages + ((size_t)p0 * hkv + g) * tile_stride;
+    const unsigned char* kt1 = (const unsigned char*)a.k_pages + ((size_t)p1 * hkv + g) * tile_stride;
+    const unsigned char* vt0 = (const unsigned char*)a.v_pages + ((size_t)p0 * hkv + g) * tile_stride;
+    const unsigned char* vt1 = (const unsigned char*)a.v_pages + ((size_t)p1 * hkv + g) * tile_stride;
+    if (tok0 + kBlockTokens <= pc.len) {
+      // whole block live: plain 16-byte loads, 1 KB per wave-wide instruction
 #pragma unroll
-    for (int j = 0; j < G_::kLoads; ++j) {
-      const int row0 = j * G_::kRowsPerLoad;                 // first token row of this load
-      const int pid = (row0 < kPageSize) ? p0 : p1;
-      const size_t off = ((size_t)pid * hkv + g) * tile_stride + (size_t)(row0 % kPageSize) * G_::kRowBytes +
-                         (size_t)lane * 16;
-      const int row = row0 + lane / G_::kChunks;
-      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (tok0 + row < pc.len) {
-        kv = *(const uint4*)((const unsigned char*)a.k_pages + off);
-        vv = *(const uint4*)((const unsigned char*)a.v_pages + off);
+      for (int j = 0; j < G_::kLoads; ++j) {
+        const int row0 = j * G_::kRowsPerLoad;
+        const int off = (row0 % kPageSize) * G_::kRowBytes + lane * 16;
+        kreg[stage][j] = *(const uint4*)((row0 < kPageSize ? kt0 : kt1) + off);
+        vreg[stage][j] = *(const uint4*)((row0 < kPageSize ? vt0 : vt1) + off);
       }
-      kreg[stage][j] = kv;
-      vreg[stage][j] = vv;
+    } else {
+      // ragged last block of a row: rows at or past L_b are neither read nor left undefined
+#pragma unroll
+      for (int j = 0; j < G_::kLoads; ++j) {
+        const int row0 = j * G_::kRowsPerLoad;
+        const int off = (row0 % kPageSize) * G_::kRowBytes + lane * 16;
+        const int row = row0 + lane / G_::kChunks;
+        uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+        if (tok0 + row < pc.len) {
+          kv = *(const uint4*)((row0 < kPageSize ? kt0 : kt1) + off);
+          vv = *(const uint4*)((row0 < kPageSize ? vt0 : vt1) + off);
+        }
+        kreg[stage][j] = kv;
+        vreg[stage][j] = vv;
+      }
     }
     // step to the next block of the run (never past its end: the rows after the last block need
     // not exist); a new row starts with a fresh page-id window

@@ -36,7 +36,8 @@ __device__ int block_exclusive_scan(int v, int* wave_tot /*[16]*/, int* total) {
 // (trajectory b, row r in [0, rows_per_b)) are laid end to end, b outermost, each with
 // n_b = ceil(L_b / kBlockTokens) blocks; the resulting sequence of T blocks is dealt to the W
 // workers in equal contiguous runs of per = ceil(T / W) blocks.  Written out: the exclusive
-// scan of n_b, the run length, T, and for every worker the (b, r, block) its run starts at.
+// scan of n_b, the run length, T, and for every worker one 16-byte record with all it needs to
+// start: (b, r << 20 | block, L_b, blocks in its run), or b = -1 for a worker without blocks.
 __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
     const int32_t* __restrict__ ctx_lens, int32_t batch, int32_t rows_per_b, int32_t workers,
     int32_t* __restrict__ header, int32_t* __restrict__ prefix, int32_t* __restrict__ wstart) {
@@ -44,6 +45,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
   __shared__ int prefix_s[kLdsPrefix + 1];
   const int tid = threadIdx.x;
   const bool in_lds = batch <= kLdsPrefix;
+  __shared__ int len_s[kLdsPrefix];
   int running = 0;
   for (int b0 = 0; b0 < batch; b0 += kPlanThreads) {
     const int b = b0 + tid;
@@ -52,7 +54,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
     const int first = running + block_exclusive_scan(count, wave_tot, &tile_total);
     if (b < batch) {
       prefix[b] = first;
-      if (in_lds) prefix_s[b] = first;
+      if (in_lds) {
+        prefix_s[b] = first;
+        len_s[b] = ctx_lens[b];
+      }
     }
     running += tile_total;
   }
@@ -72,7 +77,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
   __syncthreads();   // prefix[] written above is read below by other threads of this workgroup
   for (int w = tid; w < workers; w += kPlanThreads) {
     const long x = (long)w * per;
-    int4 st = make_int4(-1, -1, -1, 0);
+    int4 st = make_int4(-1, 0, 0, 0);
     if (x < total) {
       // largest b with rows_per_b * prefix[b] <= x (rows without blocks can never be the answer
       // because the next row then starts at the same position)
@@ -84,7 +89,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
       }
       const int n = pf[lo + 1] - pf[lo];
       const int rem = (int)(x - (long)rows_per_b * pf[lo]);
-      st = make_int4(lo, rem / n, rem % n, n);
+      const int mine = (int)min((long)per, (long)total - x);
+      st = make_int4(lo, ((rem / n) << 20) | (rem % n), in_lds ? len_s[lo] : ctx_lens[lo], mine);
     }
     *(int4*)(wstart + 4 * w) = st;
   }

@@ -376,7 +376,8 @@ def test_split_plan_covers_every_block_once_in_equal_runs():
         assert len(seen) == total                                   # every block exactly once
         for w, pieces in by_worker.items():
             assert sum(p[3] for p in pieces) == min(per, total - w * per)   # equal runs
-            assert tuple(starts[w][:3]) == pieces[0][:3]
+            assert (starts[w][0], starts[w][1] >> 20, starts[w][1] & 0xFFFFF) == pieces[0][:3]
+            assert starts[w][2] == lens[pieces[0][0]] and starts[w][3] == sum(p[3] for p in pieces)
             for i, (b, r, k, cnt, slot) in enumerate(pieces):
                 whole = k == 0 and cnt == n_blocks[b]
                 assert slot == (-1 if whole else (0 if i == 0 else 1))

@@ -1,11 +1,13 @@
 // Observation-append attention (chunked causal prefill on a cached prefix) for bf16 queries
 // over bf16 or FP8-E4M3 paged KV, on the gfx950 matrix cores.
 //
-// One workgroup = 256 query rows of one (trajectory, KV head): a row is a (chunk token, query
+// One workgroup = 128 query rows of one (trajectory, KV head): a row is a (chunk token, query
 // head of the group) pair, token-major, so the G heads that share the KV head reuse every K/V
-// tile.  Eight waves of 32 rows each walk the visible KV range in 64-token blocks (four
+// tile.  Four waves of 32 rows each walk the visible KV range in 64-token blocks (four
 // pages) that the workgroup stages once through LDS (double buffered, global loads for the
-// next block in flight while the current one is consumed).  FP8 pools are widened to bf16
+// next block in flight while the current one is consumed).  Two such workgroups share a compute
+// unit and run out of step with each other, so one's matrix products overlap the other's
+// exponentials.  FP8 pools are widened to bf16
 // while staging, so the tiles in LDS always hold bf16; page scales are applied in float to
 // S (K scale) and to P (V scale).  Per 32-token sub-block a wave computes
 //   S^T = K Q^T        tokens x rows, v_mfma_f32_32x32x16_bf16, K rows as A operand
@@ -13,6 +15,8 @@
 // The transposed products keep "row" on the lane axis in both accumulators: the softmax
 // state is one scalar per lane (shared by two lanes) and P goes from accumulator registers
 // straight into the B operand of the second product.
+#include <type_traits>
+
 #include "rollattn_internal.h"
 
 namespace rollattn {
@@ -26,12 +30,14 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 512;
+constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kRowsPerWave = 32;
-constexpr int kTileRows = kWaves * kRowsPerWave;   // 256
+static_assert(kWaves * kRowsPerWave == kAppendTileRows, "tile rows");
 constexpr int kBlockTokens = 64;                   // KV tokens staged per step
+constexpr float kSlack = 8.f;                      // log2 of the largest p tolerated before rescaling
 
 // Row t of an S^T tile holds this token of its 16-token group: the middle two quads are
 // swapped so that the 8 scores a lane ends up with are 8 consecutive tokens.
@@ -46,8 +52,8 @@ __device__ __forceinline__ float xor32_add(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-__device__ __forceinline__ void fp8x16_to_bf16(const uint4 raw, uint4& lo, uint4& hi) {
-  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+__device__ __forceinline__ void fp8x16_to_bf16(const uintx4 raw, uintx4& lo, uintx4& hi) {
+  const uint32_t w[4] = {raw[0], raw[1], raw[2], raw[3]};
   uint32_t o[8];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -59,12 +65,12 @@ __device__ __forceinline__ void fp8x16_to_bf16(const uint4 raw, uint4& lo, uint4
     o[2 * i] = __builtin_bit_cast(uint32_t, pa);
     o[2 * i + 1] = __builtin_bit_cast(uint32_t, pb);
   }
-  lo = make_uint4(o[0], o[1], o[2], o[3]);
-  hi = make_uint4(o[4], o[5], o[6], o[7]);
+  lo = uintx4{o[0], o[1], o[2], o[3]};
+  hi = uintx4{o[4], o[5], o[6], o[7]};
 }
 
 template <int D, bool FP8>
-__global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void append_mfma_kernel(const AppendArgs a) {
   constexpr int kRowBytes = D * 2;                 // bf16 rows in LDS
   constexpr int kChunks = kRowBytes / 16;          // 16-byte chunks per LDS row
   constexpr int kTileBytes = kBlockTokens * kRowBytes;
@@ -133,28 +139,43 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  const bool positive_scale = a.scale_log2 > 0.f;   // the usual case; FP8 page scales are positive too
 
   // ---- staging: thread's share of a 64-token block
-  uint4 kreg[kLoads], vreg[kLoads];
-  auto issue = [&](int blk) {
+  const int live_pages = (ctx + kPageSize - 1) / kPageSize;
+  uintx4 kreg[2][kLoads], vreg[2][kLoads];   // two blocks in flight
+  float ksc_r[2][kLoads], vsc_r[2][kLoads];  // FP8: scales of the page each wave-wide load came from
+  // Branch-free on purpose: with every load in one straight line the hardware counter the K/V loads
+  // are tracked with can be waited on partially, which is what keeps two blocks in flight.  Rows at
+  // or past L_b (ragged last block, or a block index clamped at the end of the loop) re-read the
+  // trajectory's last token instead: finite data that the causal / length mask never lets through.
+  const int last_slot = (ctx - 1) % kPageSize;
+  auto issue = [&](int blk, auto slot_c) __attribute__((always_inline)) {
+    constexpr int slot = decltype(slot_c)::value;
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
       const int idx = j * kThreads + tid;               // 16-byte chunk index within the block
       const int trow = idx / kSrcChunks;                // token row within the block
       const int c = idx % kSrcChunks;
-      const int tok = blk * kBlockTokens + trow;
-      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (trow < kBlockTokens && tok < ctx) {
-        const int pid = table[tok / kPageSize];
-        const size_t off = ((size_t)pid * hkv + g) * tile_stride + (size_t)(tok % kPageSize) * kSrcRowBytes + c * 16;
-        kv = *(const uint4*)((const unsigned char*)a.k_pages + off);
-        vv = *(const uint4*)((const unsigned char*)a.v_pages + off);
+      // the 64 chunks a wave fetches with one instruction lie in one page: its id is a scalar
+      const int pg = blk * (kBlockTokens / kPageSize) + ((j * kThreads + wave * 64) / kSrcChunks) / kPageSize;
+      const int pid = table[min(pg, live_pages - 1)];
+      if (FP8) {
+        ksc_r[slot][j] = a.k_scale[pid];
+        vsc_r[slot][j] = a.v_scale[pid];
       }
-      kreg[j] = kv;
-      vreg[j] = vv;
+      int tslot = trow % kPageSize;
+      if (pg >= live_pages - 1) tslot = min(tslot, last_slot);
+      const size_t off = ((size_t)pid * hkv + g) * tile_stride + (size_t)tslot * kSrcRowBytes + c * 16;
+      if (kBlockTokens * kSrcChunks >= kThreads || trow < kBlockTokens) {
+        kreg[slot][j] = *(const uintx4*)((const unsigned char*)a.k_pages + off);
+        vreg[slot][j] = *(const uintx4*)((const unsigned char*)a.v_pages + off);
+      }
     }
   };
-  auto commit = [&](int blk, int buf) {
+  auto commit = [&](int blk, auto slot_c) __attribute__((always_inline)) {
+    constexpr int slot = decltype(slot_c)::value;   // register slot and LDS buffer have the same parity
+    constexpr int buf = slot;
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
       const int idx = j * kThreads + tid;
@@ -164,35 +185,49 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         unsigned char* krow = k_lds[buf] + trow * kRowBytes;
         unsigned char* vrow = v_lds[buf] + trow * kRowBytes;
         const int kkey = trow & 15;
-        const int vkey = (trow & 7) << 1;
+        const int vkey = (trow & 3) << 2;
         if (FP8) {
-          uint4 lo, hi;
-          fp8x16_to_bf16(kreg[j], lo, hi);
-          *(uint4*)(krow + (((2 * c) ^ kkey) & (kChunks - 1)) * 16) = lo;
-          *(uint4*)(krow + (((2 * c + 1) ^ kkey) & (kChunks - 1)) * 16) = hi;
-          fp8x16_to_bf16(vreg[j], lo, hi);
-          *(uint4*)(vrow + (((2 * c) ^ vkey) & (kChunks - 1)) * 16) = lo;
-          *(uint4*)(vrow + (((2 * c + 1) ^ vkey) & (kChunks - 1)) * 16) = hi;
+          uintx4 lo, hi;
+          fp8x16_to_bf16(kreg[slot][j], lo, hi);
+          *(uintx4*)(krow + (((2 * c) ^ kkey) & (kChunks - 1)) * 16) = lo;
+          *(uintx4*)(krow + (((2 * c + 1) ^ kkey) & (kChunks - 1)) * 16) = hi;
+          fp8x16_to_bf16(vreg[slot][j], lo, hi);
+          *(uintx4*)(vrow + (((2 * c) ^ vkey) & (kChunks - 1)) * 16) = lo;
+          *(uintx4*)(vrow + (((2 * c + 1) ^ vkey) & (kChunks - 1)) * 16) = hi;
         } else {
-          *(uint4*)(krow + ((c ^ kkey) & (kChunks - 1)) * 16) = kreg[j];
-          *(uint4*)(vrow + ((c ^ vkey) & (kChunks - 1)) * 16) = vreg[j];
+          *(uintx4*)(krow + ((c ^ kkey) & (kChunks - 1)) * 16) = kreg[slot][j];
+          *(uintx4*)(vrow + ((c ^ vkey) & (kChunks - 1)) * 16) = vreg[slot][j];
         }
       }
     }
-    if (FP8 && tid < kBlockTokens / kPageSize) {
-      const int tok = blk * kBlockTokens + tid * kPageSize;
-      float ks = 1.f, vs = 1.f;
-      if (tok < ctx) {
-        const int pid = table[tok / kPageSize];
-        ks = a.k_scale[pid];
-        vs = a.v_scale[pid];
+    if (FP8 && lane == 0) {
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j) {
+        const int page = ((j * kThreads + wave * 64) / kSrcChunks) / kPageSize;   // page within the block
+        kscale_s[buf][page] = ksc_r[slot][j];
+        vscale_s[buf][page] = vsc_r[slot][j];
       }
-      kscale_s[buf][tid] = ks;
-      vscale_s[buf][tid] = vs;
     }
   };
 
-  auto compute = [&](int blk, int buf) {
+  // Per-lane LDS byte offsets that do not change over the loop: the K row this lane feeds as an A
+  // operand for each 16-dim step, and the V row / column pair it addresses in each transposed
+  // read.  Everything else (buffer, sub-block, token group) is a compile-time immediate.
+  int koff[kKK], voff[kDT];
+  {
+    const int t = (n32 & 16) + tau(n32 & 15);
+#pragma unroll
+    for (int kk = 0; kk < kKK; ++kk) koff[kk] = t * kRowBytes + (((kk * 2 + h2) ^ (t & 15)) & (kChunks - 1)) * 16;
+    const int j = lane & 15;
+    const int tv = h2 * 8 + (j >> 2);
+#pragma unroll
+    for (int dt = 0; dt < kDT; ++dt)
+      voff[dt] = tv * kRowBytes +
+                 (((dt * 4 + ((lane >> 4) & 1) * 2 + ((j & 3) >> 1)) ^ ((tv & 3) << 2)) & (kChunks - 1)) * 16 + (j & 1) * 8;
+  }
+
+  auto compute = [&](int blk, auto buf_c) __attribute__((always_inline)) {
+    constexpr int buf = decltype(buf_c)::value;
 #pragma unroll
     for (int sub = 0; sub < kBlockTokens / 32; ++sub) {
       const int tok0 = blk * kBlockTokens + sub * 32;
@@ -201,57 +236,59 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
       floatx16 s;
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[i] = 0.f;
-      {
-        const int t = sub * 32 + (n32 & 16) + tau(n32 & 15);
-        const unsigned char* rowp = k_lds[buf] + t * kRowBytes;
-        const int key = t & 15;
 #pragma unroll
-        for (int kk = 0; kk < kKK; ++kk) {
-          const int c = ((kk * 2 + h2) ^ key) & (kChunks - 1);
-          const bf16x8 kop = *(const bf16x8*)(rowp + c * 16);
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qop[kk], s, 0, 0, 0);
-        }
+      for (int kk = 0; kk < kKK; ++kk) {
+        const bf16x8 kop = *(const bf16x8*)(k_lds[buf] + sub * 32 * kRowBytes + koff[kk]);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qop[kk], s, 0, 0, 0);
       }
-      // register i of this lane is token tok0 + (i/8)*16 + h2*8 + (i%8) of row n32
-      float x[16];
-      const bool need_mask = tok0 + 31 > wave_min_pos;
+      // register i of this lane is token tok0 + (i/8)*16 + h2*8 + (i%8) of row n32.  Scores stay
+      // unscaled in s; the scale (and, for FP8, the K scale of the token's page) is folded into the
+      // exponent with one fused multiply-add per element: p = 2^(s * sc - m).
+      float sc[2];
+      sc[0] = FP8 ? a.scale_log2 * kscale_s[buf][sub * 2] : a.scale_log2;
+      sc[1] = FP8 ? a.scale_log2 * kscale_s[buf][sub * 2 + 1] : a.scale_log2;
+      if (!positive_scale) {                             // rare: scale the scores themselves instead
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float sc = a.scale_log2;
-        if (FP8) sc *= kscale_s[buf][sub * 2 + (i >> 3)];
-        x[i] = s[i] * sc;
+        for (int i = 0; i < 16; ++i) s[i] *= sc[i >> 3];
+        sc[0] = sc[1] = 1.f;
       }
-      if (need_mask) {
+      if (tok0 + 31 > wave_min_pos) {                    // causal edge or ragged end inside this sub-block
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int tok = tok0 + (i >> 3) * 16 + h2 * 8 + (i & 7);
-          if (tok > my_pos) x[i] = -INFINITY;
+          if (tok > my_pos) s[i] = -INFINITY;
         }
       }
-      float mx = x[0];
-#pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
-      mx = xor32_max(mx);
-      const float m_new = fmaxf(m_run, mx);
-      // rows that see nothing yet (padding rows, or causal rows ahead of this block) keep -inf
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-      float psum = 0.f;
-      bf16x8 pop[2];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float p = __builtin_amdgcn_exp2f(x[i] - m_safe);
-        psum += p;
-        pop[i >> 3][i & 7] = (__bf16)(FP8 ? p * vscale_s[buf][sub * 2 + (i >> 3)] : p);
-      }
-      l_run = l_run * alpha + psum;
-      if (__builtin_amdgcn_ballot_w64(m_new > m_run)) {
+      // sc > 0 here, so the row maximum can be taken on the unscaled scores of each page
+      float m0 = fmaxf(fmaxf(s[0], s[1]), s[2]), m1 = fmaxf(fmaxf(s[8], s[9]), s[10]);
+      m0 = fmaxf(fmaxf(m0, s[3]), s[4]); m1 = fmaxf(fmaxf(m1, s[11]), s[12]);
+      m0 = fmaxf(fmaxf(m0, s[5]), s[6]); m1 = fmaxf(fmaxf(m1, s[13]), s[14]);
+      m0 = fmaxf(m0, s[7]); m1 = fmaxf(m1, s[15]);
+      const float mx = xor32_max(fmaxf(m0 * sc[0], m1 * sc[1]));
+      // The reference maximum only moves when a row's scores exceed it by more than 2^kSlack: until
+      // then p may be as large as 2^kSlack, which float sums and bf16 P hold without loss, and the
+      // accumulators are left alone.
+      const bool bump = mx > m_run + kSlack;             // also true for the first live block (-inf)
+      const float m_new = bump ? mx : m_run;
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;   // rows that see nothing yet
+      if (__builtin_amdgcn_ballot_w64(bump)) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        l_run *= alpha;
 #pragma unroll
         for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
           for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
+        m_run = m_new;
       }
-      m_run = m_new;
+      float psum = 0.f;
+      bf16x8 pop[2];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], sc[i >> 3], -m_safe));
+        psum += p;
+        pop[i >> 3][i & 7] = (__bf16)(FP8 ? p * vscale_s[buf][sub * 2 + (i >> 3)] : p);
+      }
+      l_run += psum;
       // ---- O^T += V^T P^T
       typedef __attribute__((address_space(3))) shortx4 lds_s4;
 #pragma unroll
@@ -261,11 +298,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
           bf16x8 vop;
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf) {
-            const int j = lane & 15;
-            const int t = sub * 32 + ks * 16 + h2 * 8 + hf * 4 + (j >> 2);
-            const int c = ((dt * 4 + ((lane >> 4) & 1) * 2 + ((j & 3) >> 1)) ^ ((t & 7) << 1)) & (kChunks - 1);
             const shortx4 raw = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_s4*)(v_lds[buf] + t * kRowBytes + c * 16 + (j & 1) * 8));
+                (lds_s4*)(v_lds[buf] + (sub * 32 + ks * 16 + hf * 4) * kRowBytes + voff[dt]));
             const bf16x4 h4 = __builtin_bit_cast(bf16x4, raw);
             vop[hf * 4 + 0] = h4[0]; vop[hf * 4 + 1] = h4[1]; vop[hf * 4 + 2] = h4[2]; vop[hf * 4 + 3] = h4[3];
           }
@@ -275,16 +309,27 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     }
   };
 
-  // ---- main loop
-  issue(0);
-  commit(0, 0);
+  // ---- main loop: block j sits in LDS buffer j & 1; its global loads were issued two iterations
+  // before it is consumed and land in register slot j & 1 in between
+  constexpr std::integral_constant<int, 0> even{};
+  constexpr std::integral_constant<int, 1> odd{};
+  // (block indices past the end are clamped: the redundant copy lands in the buffer nobody reads)
+  const int last_blk = n_blocks - 1;
+  issue(0, even);
+  issue(min(1, last_blk), odd);
+  commit(0, even);
   __syncthreads();
-  for (int blk = 0; blk < n_blocks; ++blk) {
-    const int buf = blk & 1;
-    if (blk + 1 < n_blocks) issue(blk + 1);
-    compute(blk, buf);
-    if (blk + 1 < n_blocks) commit(blk + 1, buf ^ 1);
+  for (int blk = 0; blk < n_blocks; blk += 2) {
+    issue(min(blk + 2, last_blk), even);
+    compute(blk, even);
+    commit(min(blk + 1, last_blk), odd);
     __syncthreads();
+    if (blk + 1 < n_blocks) {
+      issue(min(blk + 3, last_blk), odd);
+      compute(blk + 1, odd);
+      commit(min(blk + 2, last_blk), even);
+      __syncthreads();
+    }
   }
 
   // ---- normalise and store: lane (row n32, half h2) owns dims dt*32 + (i/4)*8 + h2*4 + i%4

@@ -238,3 +238,20 @@ def test_mixed_step_scaled_down():
     dec, app = b.select(b.decode_rows()), b.select(b.append_rows())
     check(gpu_decode(dec), oracle_decode(dec), "bf16", "mixed/decode")
     check(gpu_append(app), oracle_append(app), "bf16", "mixed/append")
+
+
+@pytest.mark.parametrize("scale", [-0.2, 0.0])
+def test_non_positive_softmax_scale(scale):
+    # sm_scale is a plain number: a negative one favours the most dissimilar keys, zero gives the
+    # (causal) running mean of V
+    for kvd in ("bf16", "fp8_e4m3"):
+        w = _wl("neg", 4, 8, 2, 128, "bf16", kvd, ("uniform", 0, 300), qlen=("uniform", 1, 150), seed=301, prefix=True)
+        b = W.build(w, DEV)
+        got = B.attn_append(b.q, b.q_lens, b.q_offsets, b.k_pages, b.v_pages, b.page_table, b.ctx_lens, sm_scale=scale,
+                            max_q_len=int(b.q_lens_host.max()), k_scale=b.k_scale, v_scale=b.v_scale)
+        ref = O.attn_append(W.raw_numpy(b.q), b.q_lens_host, **dict(oracle_args(b), sm_scale=scale))
+        check(got, ref, "bf16", f"append scale {scale} {kvd}")
+        dec = B.attn_decode(b.q[: w.batch].contiguous(), b.k_pages, b.v_pages, b.page_table, b.ctx_lens, sm_scale=scale,
+                            k_scale=b.k_scale, v_scale=b.v_scale)
+        ref = O.attn_decode(W.raw_numpy(b.q[: w.batch].contiguous()), **dict(oracle_args(b), sm_scale=scale))
+        check(dec, ref, "bf16", f"decode scale {scale} {kvd}")

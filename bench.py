@@ -150,7 +150,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4 or c5")
+    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4 or c5 (or `copy`: 1 GiB copy for counter calibration)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -167,6 +167,15 @@ def main():
     B.lib()   # fail loudly if the HIP library is not built
     dev = "cuda:0"
 
+    if a.only == "copy":
+        # counter calibration: a plain device-to-device copy of known size (1 GiB read, 1 GiB written)
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(max(1, a.steps)):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "copy", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": max(1, a.steps)}))
+        return
     selected = [int(a.only.lstrip("c"))] if a.only else [HEADLINE, 3, 4, 5]
     reports = {}
     headline = None

@@ -1,0 +1,91 @@
+"""Full-size parity: the four benchmark workloads exactly as bench.py launches them (same batches,
+same entry points, same workspace sizing), checked against the oracle on sampled trajectories that
+the oracle can afford one by one: the shortest, the longest and a few seeded random ones."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_22560_amd import binding as B
+from paper_2512_22560_amd import workloads as W
+from tests.gpu_common import check, gpu_append, gpu_decode, oracle_append, oracle_decode
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _sample(batch, n_random, seed, cost=None, budget=None):
+    lens = batch.ctx_lens_host
+    rows = {int(np.argmin(lens)), int(np.argmax(lens))}
+    rng = np.random.default_rng(seed)
+    for r in rng.permutation(len(lens)):
+        if len(rows) >= n_random + 2:
+            break
+        rows.add(int(r))
+    rows = sorted(rows)
+    if cost is not None:                       # keep the oracle's work bounded
+        rows = sorted(rows, key=lambda r: cost[r])
+        keep, spent = [], 0
+        for r in rows:
+            if not keep or spent + cost[r] <= budget:
+                keep.append(r)
+                spent += cost[r]
+        rows = sorted(keep)
+    return np.asarray(rows)
+
+
+def _rows_of(batch, rows):
+    offs = np.concatenate([[0], np.cumsum(batch.q_lens_host)])
+    return np.concatenate([np.arange(offs[r], offs[r + 1]) for r in rows])
+
+
+@pytest.mark.parametrize("c", [2, 3])
+def test_decode_workloads_full_size(c):
+    b = W.build(W.CONFIGS[c], DEV)
+    out = gpu_decode(b)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    rows = _sample(b, 8, seed=c)
+    sub = b.select(rows)
+    ref = oracle_decode(sub)
+    check(out[torch.from_numpy(rows).to(DEV)], ref, "bf16", f"config {c} rows {rows.tolist()}")
+
+
+def test_append_workload_full_size():
+    b = W.build(W.CONFIGS[4], DEV)
+    out = gpu_append(b)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    cost = b.q_lens_host * b.ctx_lens_host
+    rows = _sample(b, 3, seed=4, cost=cost, budget=2.0e7)
+    sub = b.select(rows)
+    ref = oracle_append(sub)
+    check(out[torch.from_numpy(_rows_of(b, rows)).to(DEV)], ref, "bf16", f"config 4 rows {rows.tolist()}")
+
+
+def test_mixed_step_full_size():
+    b = W.build(W.CONFIGS[5], DEV)
+    dec, app = b.select(b.decode_rows()), b.select(b.append_rows())
+    out_d = gpu_decode(dec)
+    out_a = gpu_append(app)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out_d.float()).all() and torch.isfinite(out_a.float()).all()
+    rows = _sample(dec, 6, seed=5)
+    check(out_d[torch.from_numpy(rows).to(DEV)], oracle_decode(dec.select(rows)), "bf16",
+          f"config 5 decode rows {rows.tolist()}")
+    cost = app.q_lens_host * app.ctx_lens_host
+    rows = _sample(app, 2, seed=6, cost=cost, budget=6.0e6)
+    check(out_a[torch.from_numpy(_rows_of(app, rows)).to(DEV)], oracle_append(app.select(rows)), "bf16",
+          f"config 5 append rows {rows.tolist()}")
+
+
+def test_workspace_is_sized_from_the_descriptor_alone():
+    # the same workspace serves any lengths the descriptor admits, e.g. every row at the maximum
+    w = W.Workload("maxlen", 16, 32, 8, 128, "bf16", "bf16", ("const", 4096), seed=9)
+    b = W.build(w, DEV)
+    desc = B.make_desc(b.q, b.k_pages, b.page_table, sm_scale=w.sm_scale)
+    ws = B.alloc_workspace(desc, b.total_q, DEV)
+    check(gpu_decode(b, workspace=ws), oracle_decode(b), "bf16", "all rows at max length")
+    short = np.full(16, 5)
+    b.ctx_lens_host = short
+    b.ctx_lens = torch.from_numpy(short.astype(np.int32)).to(DEV)
+    check(gpu_decode(b, workspace=ws), oracle_decode(b), "bf16", "same workspace, short rows")

@@ -35,7 +35,7 @@
  *                                               of its physical page (per pool)
  * Supported element types: q/out F32 with kv F32 (D = 64 or 128); q/out BF16 with kv
  * BF16 or FP8_E4M3 (OCP E4M3, no infinities, max 448; D = 64 or 128).  Accumulation
- * is float.  Hq / Hkv may be any positive integer (at most 128 for BF16 attn_append).
+ * is float.  Hq / Hkv may be any positive integer (at most 256 for BF16 attn_append).
  *
  * Execution.  Calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*,
  * NULL = the default stream) and return without synchronising; nothing is copied to

@@ -1,13 +1,11 @@
 // Observation-append attention (chunked causal prefill on a cached prefix) for bf16 queries
 // over bf16 or FP8-E4M3 paged KV, on the gfx950 matrix cores.
 //
-// One workgroup = 128 query rows of one (trajectory, KV head): a row is a (chunk token, query
+// One workgroup = 256 query rows of one (trajectory, KV head): a row is a (chunk token, query
 // head of the group) pair, token-major, so the G heads that share the KV head reuse every K/V
-// tile.  Four waves of 32 rows each walk the visible KV range in 64-token blocks (four
-// pages) that the workgroup stages once through LDS (double buffered, global loads for the
-// next block in flight while the current one is consumed).  Two such workgroups share a compute
-// unit and run out of step with each other, so one's matrix products overlap the other's
-// exponentials.  FP8 pools are widened to bf16
+// tile.  Eight waves of 32 rows each walk the visible KV range in 64-token blocks (four
+// pages) that the workgroup stages once through LDS (double buffered, global loads two
+// blocks ahead of the one being consumed).  FP8 pools are widened to bf16
 // while staging, so the tiles in LDS always hold bf16; page scales are applied in float to
 // S (K scale) and to P (V scale).  Per 32-token sub-block a wave computes
 //   S^T = K Q^T        tokens x rows, v_mfma_f32_32x32x16_bf16, K rows as A operand
@@ -32,7 +30,7 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kRowsPerWave = 32;
 static_assert(kWaves * kRowsPerWave == kAppendTileRows, "tile rows");
@@ -70,7 +68,7 @@ __device__ __forceinline__ void fp8x16_to_bf16(const uintx4 raw, uintx4& lo, uin
 }
 
 template <int D, bool FP8>
-__global__ __launch_bounds__(kThreads, 2) void append_mfma_kernel(const AppendArgs a) {
+__global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs a) {
   constexpr int kRowBytes = D * 2;                 // bf16 rows in LDS
   constexpr int kChunks = kRowBytes / 16;          // 16-byte chunks per LDS row
   constexpr int kTileBytes = kBlockTokens * kRowBytes;
@@ -204,8 +202,10 @@ __global__ __launch_bounds__(kThreads, 2) void append_mfma_kernel(const AppendAr
 #pragma unroll
       for (int j = 0; j < kLoads; ++j) {
         const int page = ((j * kThreads + wave * 64) / kSrcChunks) / kPageSize;   // page within the block
-        kscale_s[buf][page] = ksc_r[slot][j];
-        vscale_s[buf][page] = vsc_r[slot][j];
+        if (page < kBlockTokens / kPageSize) {
+          kscale_s[buf][page] = ksc_r[slot][j];
+          vscale_s[buf][page] = vsc_r[slot][j];
+        }
       }
     }
   };

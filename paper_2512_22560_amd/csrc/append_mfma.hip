@@ -147,14 +147,23 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   // are tracked with can be waited on partially, which is what keeps two blocks in flight.  Rows at
   // or past L_b (ragged last block, or a block index clamped at the end of the loop) re-read the
   // trajectory's last token instead: finite data that the causal / length mask never lets through.
+  // Per thread and load, the byte offset inside a (page, head) tile never changes: only the page
+  // does, and that is a scalar.  Two variants, the second with the row clamped to the last live slot
+  // for loads that fall in (or past) the trajectory's last page.
   const int last_slot = (ctx - 1) % kPageSize;
+  unsigned int goff[kLoads], goff_last[kLoads];
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    const int idx = j * kThreads + tid;               // 16-byte chunk index within the block
+    const int tslot = (idx / kSrcChunks) % kPageSize; // token slot within its page
+    const int c = idx % kSrcChunks;
+    goff[j] = tslot * kSrcRowBytes + c * 16;
+    goff_last[j] = min(tslot, last_slot) * kSrcRowBytes + c * 16;
+  }
   auto issue = [&](int blk, auto slot_c) __attribute__((always_inline)) {
     constexpr int slot = decltype(slot_c)::value;
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
-      const int idx = j * kThreads + tid;               // 16-byte chunk index within the block
-      const int trow = idx / kSrcChunks;                // token row within the block
-      const int c = idx % kSrcChunks;
       // the 64 chunks a wave fetches with one instruction lie in one page: its id is a scalar
       const int pg = blk * (kBlockTokens / kPageSize) + ((j * kThreads + wave * 64) / kSrcChunks) / kPageSize;
       const int pid = table[min(pg, live_pages - 1)];
@@ -162,12 +171,11 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         ksc_r[slot][j] = a.k_scale[pid];
         vsc_r[slot][j] = a.v_scale[pid];
       }
-      int tslot = trow % kPageSize;
-      if (pg >= live_pages - 1) tslot = min(tslot, last_slot);
-      const size_t off = ((size_t)pid * hkv + g) * tile_stride + (size_t)tslot * kSrcRowBytes + c * 16;
-      if (kBlockTokens * kSrcChunks >= kThreads || trow < kBlockTokens) {
-        kreg[slot][j] = *(const uintx4*)((const unsigned char*)a.k_pages + off);
-        vreg[slot][j] = *(const uintx4*)((const unsigned char*)a.v_pages + off);
+      const size_t tile_off = ((size_t)pid * hkv + g) * tile_stride;     // scalar
+      const unsigned int off = (pg >= live_pages - 1) ? goff_last[j] : goff[j];
+      if (kBlockTokens * kSrcChunks >= kThreads || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
+        kreg[slot][j] = *(const uintx4*)((const unsigned char*)a.k_pages + tile_off + off);
+        vreg[slot][j] = *(const uintx4*)((const unsigned char*)a.v_pages + tile_off + off);
       }
     }
   };

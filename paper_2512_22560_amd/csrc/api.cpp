@@ -326,7 +326,7 @@ int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q
     if (e != hipSuccess) return fail_hip(e);
     return ROLLATTN_OK;
   }
-  e = launch_plan_append(q_lens, desc->batch, a.tile_tokens, w.workers, a.header, (int32_t*)(base + w.wstart),
+  e = launch_plan_append(q_lens, ctx_lens, desc->batch, a.tile_tokens, w.workers, a.header, (int32_t*)(base + w.wstart),
                          (int32_t*)(base + w.tile_q0), s);
   if (e != hipSuccess) return fail_hip(e);
   {

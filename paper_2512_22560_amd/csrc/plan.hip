@@ -96,17 +96,41 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
   }
 }
 
-// Append work list: each chunk cut into tiles of tile_tokens query tokens.
+// Append work list: each chunk cut into tiles of tile_tokens query tokens.  A tile's cost grows
+// with its trajectory's context, and workgroups are dispatched in list order, so (for batches that
+// fit the ranking in LDS) trajectories are listed longest context first: the long tiles start
+// early and the short ones fill the tail.
+constexpr int kRankBatch = 4096;
 __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
-    const int32_t* __restrict__ q_lens, int32_t batch, int32_t tile_tokens, int32_t cap,
-    int32_t* __restrict__ header, int32_t* __restrict__ tile_b, int32_t* __restrict__ tile_q0) {
+    const int32_t* __restrict__ q_lens, const int32_t* __restrict__ ctx_lens, int32_t batch, int32_t tile_tokens,
+    int32_t cap, int32_t* __restrict__ header, int32_t* __restrict__ tile_b, int32_t* __restrict__ tile_q0) {
   __shared__ int wave_tot[kPlanThreads / 64];
+  __shared__ int len_s[kRankBatch];
+  __shared__ int order_s[kRankBatch];
   const int tid = threadIdx.x;
+  const bool ranked = batch <= kRankBatch;
+  if (ranked) {
+    for (int b = tid; b < batch; b += kPlanThreads) len_s[b] = ctx_lens[b];
+    __syncthreads();
+    for (int b = tid; b < batch; b += kPlanThreads) {
+      const int mine = len_s[b];
+      int rank = 0;
+      for (int o = 0; o < batch; ++o) {
+        const int other = len_s[o];
+        rank += (other > mine || (other == mine && o < b)) ? 1 : 0;
+      }
+      order_s[rank] = b;
+    }
+    __syncthreads();
+  }
   int running = 0;
-  for (int b0 = 0; b0 < batch; b0 += kPlanThreads) {
-    const int b = b0 + tid;
-    int count = 0;
-    if (b < batch) count = (q_lens[b] + tile_tokens - 1) / tile_tokens;
+  for (int p0 = 0; p0 < batch; p0 += kPlanThreads) {
+    const int p = p0 + tid;
+    int b = 0, count = 0;
+    if (p < batch) {
+      b = ranked ? order_s[p] : p;
+      count = (q_lens[b] + tile_tokens - 1) / tile_tokens;
+    }
     int tile_total;
     const int first = running + block_exclusive_scan(count, wave_tot, &tile_total);
     for (int s = 0; s < count; ++s) {
@@ -129,9 +153,9 @@ hipError_t launch_plan_decode(const int32_t* ctx_lens, int32_t batch, int32_t ro
   return hipGetLastError();
 }
 
-hipError_t launch_plan_append(const int32_t* q_lens, int32_t batch, int32_t tile_tokens, int32_t cap,
-                              int32_t* header, int32_t* tile_b, int32_t* tile_q0, hipStream_t s) {
-  hipLaunchKernelGGL(plan_append_kernel, dim3(1), dim3(kPlanThreads), 0, s, q_lens, batch, tile_tokens, cap,
+hipError_t launch_plan_append(const int32_t* q_lens, const int32_t* ctx_lens, int32_t batch, int32_t tile_tokens,
+                              int32_t cap, int32_t* header, int32_t* tile_b, int32_t* tile_q0, hipStream_t s) {
+  hipLaunchKernelGGL(plan_append_kernel, dim3(1), dim3(kPlanThreads), 0, s, q_lens, ctx_lens, batch, tile_tokens, cap,
                      header, tile_b, tile_q0);
   return hipGetLastError();
 }

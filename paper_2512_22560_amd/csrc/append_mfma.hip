@@ -14,6 +14,34 @@
 // state is one scalar per lane (shared by two lanes) and P goes from accumulator registers
 // straight into the B operand of the second product.
 #include <type_traits>
+#include <utility>
+#ifndef PP_ORDER
+#define PP_ORDER 0
+#endif
+#ifndef PP_SALU
+#define PP_SALU 3
+#endif
+#ifndef PP_VALU
+#define PP_VALU 2
+#endif
+#ifndef PP_AHEAD
+#define PP_AHEAD 4
+#endif
+#ifndef PP_SCHED
+#define PP_SCHED 1
+#endif
+#ifndef PP_GRP
+#define PP_GRP 0
+#endif
+#ifndef PP_TIME
+#define PP_TIME 0
+#endif
+#ifndef PP_PIN
+#define PP_PIN 1
+#endif
+#ifndef PP_PRIO
+#define PP_PRIO 1
+#endif
 
 #include "rollattn_internal.h"
 
@@ -67,6 +95,15 @@ __device__ __forceinline__ void fp8x16_to_bf16(const uintx4 raw, uintx4& lo, uin
   hi = uintx4{o[4], o[5], o[6], o[7]};
 }
 
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 template <int D, bool FP8>
 __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs a) {
   constexpr int kRowBytes = D * 2;                 // bf16 rows in LDS
@@ -79,10 +116,11 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   constexpr int kDT = D / 32;                      // 32-wide output tiles along D
   static_assert((kBlockTokens * kSrcChunks) % kThreads == 0 || kBlockTokens * kSrcChunks < kThreads, "staging shape");
 
-  __shared__ __attribute__((aligned(16))) unsigned char k_lds[2][kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char v_lds[2][kTileBytes];
-  __shared__ float kscale_s[2][kBlockTokens / kPageSize];
-  __shared__ float vscale_s[2][kBlockTokens / kPageSize];
+  // bf16 pools go from HBM straight into LDS (no register stop), which needs a ring of three tiles
+  // per pool to give the loads time; FP8 pools pass through registers to be widened, two tiles.
+  constexpr int kRing = FP8 ? 2 : 3;
+  __shared__ __attribute__((aligned(1024))) unsigned char k_lds[kRing][kTileBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char v_lds[kRing][kTileBytes];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -106,7 +144,13 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   const int pos0 = ctx - n_b + q0;                       // position of the tile's first token
   const int kv_end = pos0 + tokens_here;                 // tokens [0, kv_end) are visible to some row
   const int n_blocks = (kv_end + kBlockTokens - 1) / kBlockTokens;
-  const int32_t* table = a.page_table + (size_t)b * a.max_pages;
+  // Page ids and page scales are inputs nobody writes during the call: reading them through the
+  // constant address space lets every such load (all uniform) take the scalar path.
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_p;
+  typedef const __attribute__((address_space(4))) float* const_f32_p;
+  const const_i32_p table = (const_i32_p)(a.page_table + (size_t)b * a.max_pages);
+  const const_f32_p k_scale_c = (const_f32_p)a.k_scale;
+  const const_f32_p v_scale_c = (const_f32_p)a.v_scale;
   const size_t tile_stride = (size_t)kPageSize * kSrcRowBytes;
 
   // ---- this lane's query row
@@ -115,10 +159,9 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   const int tok_in_tile = row / group;
   const int head = g * group + (row - tok_in_tile * group);
   const int my_pos = row_ok ? pos0 + tok_in_tile : -1;   // last visible token of this row
-  // wave-uniform bounds for skipping fully masked sub-blocks
-  const int wave_last_row = min(wave * kRowsPerWave + kRowsPerWave - 1, rows_here - 1);
-  const int wave_max_pos = (wave * kRowsPerWave < rows_here) ? pos0 + wave_last_row / group : -1;
-  const int wave_min_pos = pos0 + (wave * kRowsPerWave) / group;
+  // blocks that end at or before this position are fully visible to every row of the wave
+  const int wave_min_pos = (wave * kRowsPerWave < rows_here) ? pos0 + (wave * kRowsPerWave) / group : -1;
+  const int grp = wave >> 2;   // 0: leading half of the workgroup, 1: the half that runs one phase behind (waves w and w + 4 share a SIMD)
 
   bf16x8 qop[kKK];
   {
@@ -139,81 +182,125 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   float m_run = -INFINITY, l_run = 0.f;
   const bool positive_scale = a.scale_log2 > 0.f;   // the usual case; FP8 page scales are positive too
 
-  // ---- staging: thread's share of a 64-token block
+  // ---- staging.  Unit u = (K block u + 1, V block u): the two tiles that the matrix phase of
+  // block u + 1 reads; block j lives in ring slot j % kRing of its pool.  Per thread and load, the
+  // byte offset inside a (page, head) tile never changes: only the page does, and that is a scalar.
+  // Branch-free on purpose (loads can then be waited on by count).  Rows at or past L_b (ragged
+  // last block, or a block index clamped at the end of the loop) re-read the trajectory's last
+  // token instead: finite data that the causal / length mask never lets through.
   const int live_pages = (ctx + kPageSize - 1) / kPageSize;
-  uintx4 kreg[2][kLoads], vreg[2][kLoads];   // two blocks in flight
-  float ksc_r[2][kLoads], vsc_r[2][kLoads];  // FP8: scales of the page each wave-wide load came from
-  // Branch-free on purpose: with every load in one straight line the hardware counter the K/V loads
-  // are tracked with can be waited on partially, which is what keeps two blocks in flight.  Rows at
-  // or past L_b (ragged last block, or a block index clamped at the end of the loop) re-read the
-  // trajectory's last token instead: finite data that the causal / length mask never lets through.
-  // Per thread and load, the byte offset inside a (page, head) tile never changes: only the page
-  // does, and that is a scalar.  Two variants, the second with the row clamped to the last live slot
-  // for loads that fall in (or past) the trajectory's last page.
+  const int last_blk = n_blocks - 1;
   const int last_slot = (ctx - 1) % kPageSize;
-  unsigned int goff[kLoads], goff_last[kLoads];
+  constexpr int kPagesPerBlock = kBlockTokens / kPageSize;
+  constexpr bool kAllThreadsLoad = kBlockTokens * kSrcChunks >= kThreads;
+  // Chunk idx = j * kThreads + tid of a block sits in LDS row idx / kChunks at chunk position
+  // (idx % kChunks), holding the row's chunk (position ^ key): key = row & 15 for K, (row & 3) << 2
+  // for V.  The register path (FP8) applies the swizzle when it writes LDS; the direct path has to
+  // apply it on the global side, because there the LDS position of a lane's chunk is fixed.
+  unsigned int goff[kLoads][2], goff_last[kLoads][2];   // [][0]: K, [][1]: V
+  int woff[kLoads][2];
 #pragma unroll
   for (int j = 0; j < kLoads; ++j) {
-    const int idx = j * kThreads + tid;               // 16-byte chunk index within the block
-    const int tslot = (idx / kSrcChunks) % kPageSize; // token slot within its page
+    const int idx = j * kThreads + tid;
+    const int trow = idx / kSrcChunks;
+    const int tslot = trow % kPageSize;               // token slot within its page
     const int c = idx % kSrcChunks;
-    goff[j] = tslot * kSrcRowBytes + c * 16;
-    goff_last[j] = min(tslot, last_slot) * kSrcRowBytes + c * 16;
+    const int kkey = trow & 15, vkey = (trow & 3) << 2;
+    const int ck = FP8 ? c : ((c ^ kkey) & (kChunks - 1)), cv = FP8 ? c : ((c ^ vkey) & (kChunks - 1));
+    goff[j][0] = tslot * kSrcRowBytes + ck * 16;
+    goff[j][1] = tslot * kSrcRowBytes + cv * 16;
+    goff_last[j][0] = min(tslot, last_slot) * kSrcRowBytes + ck * 16;
+    goff_last[j][1] = min(tslot, last_slot) * kSrcRowBytes + cv * 16;
+    woff[j][0] = trow * kRowBytes + (((2 * c) ^ kkey) & (kChunks - 1)) * 16;   // FP8 only
+    woff[j][1] = trow * kRowBytes + (((2 * c) ^ vkey) & (kChunks - 1)) * 16;
   }
-  auto issue = [&](int blk, auto slot_c) __attribute__((always_inline)) {
+  // The 64 chunks a wave fetches with one instruction lie in one page, so its id is a scalar.
+  // fetch_pids: the page ids behind this wave's kLoads loads of one block (block index clamped to
+  // the last block, page index to the last live page).
+  int pj[kLoads];
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) pj[j] = ((j * kThreads + wave * 64) / kSrcChunks) / kPageSize;
+  auto fetch_pids = [&](int blk, int* dst) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) dst[j] = table[min(min(blk, last_blk) * kPagesPerBlock + pj[j], live_pages - 1)];
+  };
+  // one wave-wide 16-byte load of block blk: scalar tile base, per-lane offset
+  struct TileAddr { const unsigned char* base; unsigned int off; };
+  auto tile_addr = [&](const void* pool, int pool_i, int blk, const int* pids, int j) __attribute__((always_inline)) -> TileAddr {
+    const int pg = min(blk, last_blk) * kPagesPerBlock + pj[j];
+    const size_t tile_off = ((size_t)pids[j] * hkv + g) * tile_stride;     // scalar
+    return TileAddr{(const unsigned char*)pool + tile_off, (pg >= live_pages - 1) ? goff_last[j][pool_i] : goff[j][pool_i]};
+  };
+  // -- register path (FP8)
+  uintx4 kreg[2][kLoads], vreg[2][kLoads];   // two units in flight
+  auto issue = [&](int u, const int* pk, const int* pv, auto slot_c) __attribute__((always_inline)) {
     constexpr int slot = decltype(slot_c)::value;
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
-      // the 64 chunks a wave fetches with one instruction lie in one page: its id is a scalar
-      const int pg = blk * (kBlockTokens / kPageSize) + ((j * kThreads + wave * 64) / kSrcChunks) / kPageSize;
-      const int pid = table[min(pg, live_pages - 1)];
-      if (FP8) {
-        ksc_r[slot][j] = a.k_scale[pid];
-        vsc_r[slot][j] = a.v_scale[pid];
-      }
-      const size_t tile_off = ((size_t)pid * hkv + g) * tile_stride;     // scalar
-      const unsigned int off = (pg >= live_pages - 1) ? goff_last[j] : goff[j];
-      if (kBlockTokens * kSrcChunks >= kThreads || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
-        kreg[slot][j] = *(const uintx4*)((const unsigned char*)a.k_pages + tile_off + off);
-        vreg[slot][j] = *(const uintx4*)((const unsigned char*)a.v_pages + tile_off + off);
+      if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
+        const TileAddr ka = tile_addr(a.k_pages, 0, u + 1, pk, j), va = tile_addr(a.v_pages, 1, u, pv, j);
+        kreg[slot][j] = *(const uintx4*)(ka.base + ka.off);
+        vreg[slot][j] = *(const uintx4*)(va.base + va.off);
       }
     }
   };
-  auto commit = [&](int blk, auto slot_c) __attribute__((always_inline)) {
-    constexpr int slot = decltype(slot_c)::value;   // register slot and LDS buffer have the same parity
-    constexpr int buf = slot;
+  auto put = [&](unsigned char* dst, const uintx4 raw) __attribute__((always_inline)) {
+    // the two 16-byte halves of the widened chunk sit in chunks 2c and 2c + 1: 16 bytes apart after the swizzle
+    uintx4 lo, hi;
+    fp8x16_to_bf16(raw, lo, hi);
+    *(uintx4*)dst = lo;
+    *(uintx4*)((unsigned char*)((uintptr_t)dst ^ 16)) = hi;
+  };
+  auto commit = [&](int u, auto slot_c) __attribute__((always_inline)) {
+    constexpr int slot = decltype(slot_c)::value;
+    unsigned char* kdst = k_lds[(u + 1) & 1];
+    unsigned char* vdst = v_lds[u & 1];
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
-      const int idx = j * kThreads + tid;
-      const int trow = idx / kSrcChunks;
-      const int c = idx % kSrcChunks;
-      if (trow < kBlockTokens) {
-        unsigned char* krow = k_lds[buf] + trow * kRowBytes;
-        unsigned char* vrow = v_lds[buf] + trow * kRowBytes;
-        const int kkey = trow & 15;
-        const int vkey = (trow & 3) << 2;
-        if (FP8) {
-          uintx4 lo, hi;
-          fp8x16_to_bf16(kreg[slot][j], lo, hi);
-          *(uintx4*)(krow + (((2 * c) ^ kkey) & (kChunks - 1)) * 16) = lo;
-          *(uintx4*)(krow + (((2 * c + 1) ^ kkey) & (kChunks - 1)) * 16) = hi;
-          fp8x16_to_bf16(vreg[slot][j], lo, hi);
-          *(uintx4*)(vrow + (((2 * c) ^ vkey) & (kChunks - 1)) * 16) = lo;
-          *(uintx4*)(vrow + (((2 * c + 1) ^ vkey) & (kChunks - 1)) * 16) = hi;
-        } else {
-          *(uintx4*)(krow + ((c ^ kkey) & (kChunks - 1)) * 16) = kreg[slot][j];
-          *(uintx4*)(vrow + ((c ^ vkey) & (kChunks - 1)) * 16) = vreg[slot][j];
-        }
+      if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
+        put(kdst + woff[j][0], kreg[slot][j]);
+        put(vdst + woff[j][1], vreg[slot][j]);
       }
     }
-    if (FP8 && lane == 0) {
+  };
+  // -- direct path (bf16): HBM -> LDS without a register stop.  Lane l's 16 bytes land at
+  // M0 + 16 l.  The compiler does not see these loads: completion is awaited by count below, and
+  // nothing else in the loop uses the vector-memory counter.  M0 is not live across statements in
+  // compiler-generated code, so it is simply overwritten.
+  auto dma = [&](const TileAddr& t, unsigned char* lds_dst) __attribute__((always_inline)) {
+    const unsigned int m0 = __builtin_amdgcn_readfirstlane((unsigned int)(uintptr_t)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(t.off), "s"(t.base));
+  };
+  auto dma_k = [&](int blk, const int* pids) __attribute__((always_inline)) {
+    unsigned char* dst = k_lds[0] + ((unsigned)blk % 3u) * kTileBytes + wave * 1024;
 #pragma unroll
-      for (int j = 0; j < kLoads; ++j) {
-        const int page = ((j * kThreads + wave * 64) / kSrcChunks) / kPageSize;   // page within the block
-        if (page < kBlockTokens / kPageSize) {
-          kscale_s[buf][page] = ksc_r[slot][j];
-          vscale_s[buf][page] = vsc_r[slot][j];
-        }
+    for (int j = 0; j < kLoads; ++j) dma(tile_addr(a.k_pages, 0, blk, pids, j), dst + j * kThreads * 16);
+  };
+  auto dma_v = [&](int blk, const int* pids) __attribute__((always_inline)) {
+    unsigned char* dst = v_lds[0] + ((unsigned)blk % 3u) * kTileBytes + wave * 1024;
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) dma(tile_addr(a.v_pages, 1, blk, pids, j), dst + j * kThreads * 16);
+  };
+#define DMA_WAIT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n))
+
+  // FP8: scales of the four pages of a block (scalar loads), folded with the softmax scale; the page
+  // ids behind them are fetched one vector phase before the scales, the scales one phase before use
+  float ksc_cur[4], vsc_cur[4];
+  int spid[kPagesPerBlock];
+  auto fetch_spids = [&](int blk) __attribute__((always_inline)) {
+#pragma unroll
+    for (int p = 0; p < kPagesPerBlock; ++p)
+      spid[p] = FP8 ? table[min(min(blk, last_blk) * kPagesPerBlock + p, live_pages - 1)] : 0;
+  };
+  auto load_scales = [&](float* ks, float* vs) __attribute__((always_inline)) {
+#pragma unroll
+    for (int p = 0; p < kPagesPerBlock; ++p) {
+      if (FP8) {
+        ks[p] = k_scale_c[spid[p]] * a.scale_log2;
+        vs[p] = v_scale_c[spid[p]];
+      } else {
+        ks[p] = a.scale_log2;
+        vs[p] = 1.f;
       }
     }
   };
@@ -234,111 +321,314 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
                  (((dt * 4 + ((lane >> 4) & 1) * 2 + ((j & 3) >> 1)) ^ ((tv & 3) << 2)) & (kChunks - 1)) * 16 + (j & 1) * 8;
   }
 
-  auto compute = [&](int blk, auto buf_c) __attribute__((always_inline)) {
-    constexpr int buf = decltype(buf_c)::value;
-#pragma unroll
-    for (int sub = 0; sub < kBlockTokens / 32; ++sub) {
-      const int tok0 = blk * kBlockTokens + sub * 32;
-      if (tok0 > wave_max_pos) continue;                 // nothing visible to this wave (uniform)
-      // ---- S^T (32 tokens x 32 rows)
-      floatx16 s;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < kKK; ++kk) {
-        const bf16x8 kop = *(const bf16x8*)(k_lds[buf] + sub * 32 * kRowBytes + koff[kk]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qop[kk], s, 0, 0, 0);
-      }
-      // register i of this lane is token tok0 + (i/8)*16 + h2*8 + (i%8) of row n32.  Scores stay
-      // unscaled in s; the scale (and, for FP8, the K scale of the token's page) is folded into the
-      // exponent with one fused multiply-add per element: p = 2^(s * sc - m).
-      float sc[2];
-      sc[0] = FP8 ? a.scale_log2 * kscale_s[buf][sub * 2] : a.scale_log2;
-      sc[1] = FP8 ? a.scale_log2 * kscale_s[buf][sub * 2 + 1] : a.scale_log2;
-      if (!positive_scale) {                             // rare: scale the scores themselves instead
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] *= sc[i >> 3];
-        sc[0] = sc[1] = 1.f;
-      }
-      if (tok0 + 31 > wave_min_pos) {                    // causal edge or ragged end inside this sub-block
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int tok = tok0 + (i >> 3) * 16 + h2 * 8 + (i & 7);
-          if (tok > my_pos) s[i] = -INFINITY;
-        }
-      }
-      // sc > 0 here, so the row maximum can be taken on the unscaled scores of each page
-      float m0 = fmaxf(fmaxf(s[0], s[1]), s[2]), m1 = fmaxf(fmaxf(s[8], s[9]), s[10]);
-      m0 = fmaxf(fmaxf(m0, s[3]), s[4]); m1 = fmaxf(fmaxf(m1, s[11]), s[12]);
-      m0 = fmaxf(fmaxf(m0, s[5]), s[6]); m1 = fmaxf(fmaxf(m1, s[13]), s[14]);
-      m0 = fmaxf(m0, s[7]); m1 = fmaxf(m1, s[15]);
-      const float mx = xor32_max(fmaxf(m0 * sc[0], m1 * sc[1]));
-      // The reference maximum only moves when a row's scores exceed it by more than 2^kSlack: until
-      // then p may be as large as 2^kSlack, which float sums and bf16 P hold without loss, and the
-      // accumulators are left alone.
-      const bool bump = mx > m_run + kSlack;             // also true for the first live block (-inf)
-      const float m_new = bump ? mx : m_run;
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;   // rows that see nothing yet
-      if (__builtin_amdgcn_ballot_w64(bump)) {
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-        l_run *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < kDT; ++dt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
-        m_run = m_new;
-      }
-      float psum = 0.f;
-      bf16x8 pop[2];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], sc[i >> 3], -m_safe));
-        psum += p;
-        pop[i >> 3][i & 7] = (__bf16)(FP8 ? p * vscale_s[buf][sub * 2 + (i >> 3)] : p);
-      }
-      l_run += psum;
-      // ---- O^T += V^T P^T
-      typedef __attribute__((address_space(3))) shortx4 lds_s4;
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-        for (int dt = 0; dt < kDT; ++dt) {
-          bf16x8 vop;
+  constexpr int kSubs = kBlockTokens / 32;
+  floatx16 s[kSubs];        // scores of the block between its two phases
+  bf16x8 pop[kSubs][2];     // its probabilities, as B operands of the second product
+
+  // ---- matrix phase: up to 32 MFMA steps, O^T += V^T P^T for the previous block (steps 0-15, V buffer
+  // vb) and S^T = K Q^T for this one (steps 16-31, K buffer kb).  Every step needs one 32x16 operand
+  // from LDS; the reads run kAhead steps in front of the MFMAs that consume them, because during
+  // this phase no second wave hides the LDS latency.  After step t the caller's piece(p0, p1) runs
+  // with [p0, p1) the slice of 32 schedule positions that the step covers: that is where the
+  // staging work of the phase is threaded between the MFMAs.
+  constexpr int kAhead = PP_AHEAD;
+  auto matrix_phase = [&](auto first_c, auto last_c, int kb, int vb, auto&& piece) __attribute__((always_inline)) {
+    constexpr int T0 = decltype(first_c)::value, T1 = decltype(last_c)::value;
+    const unsigned char* kbuf = k_lds[0] + kb * kTileBytes;
+    const unsigned char* vbuf = v_lds[0] + vb * kTileBytes;
+    typedef __attribute__((address_space(3))) shortx4 lds_s4;
+    bf16x8 ops[32];
+    auto fetch = [&](auto t_c) __attribute__((always_inline)) {
+      constexpr int t = decltype(t_c)::value;
+      if constexpr (t < 16) {
+        constexpr int sub = t >> 3, ks = (t >> 2) & 1, dt = t & 3;
+        if constexpr (dt < kDT) {
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf) {
             const shortx4 raw = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_s4*)(v_lds[buf] + (sub * 32 + ks * 16 + hf * 4) * kRowBytes + voff[dt]));
+                (lds_s4*)(vbuf + (sub * 32 + ks * 16 + hf * 4) * kRowBytes + voff[dt]));
             const bf16x4 h4 = __builtin_bit_cast(bf16x4, raw);
-            vop[hf * 4 + 0] = h4[0]; vop[hf * 4 + 1] = h4[1]; vop[hf * 4 + 2] = h4[2]; vop[hf * 4 + 3] = h4[3];
+            ops[t][hf * 4 + 0] = h4[0]; ops[t][hf * 4 + 1] = h4[1]; ops[t][hf * 4 + 2] = h4[2]; ops[t][hf * 4 + 3] = h4[3];
           }
-          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], acc[dt], 0, 0, 0);
+        }
+      } else {
+        constexpr int u = t - 16, kk = u >> 1, sub = u & 1;
+        if constexpr (kk < kKK) ops[t] = *(const bf16x8*)(kbuf + sub * 32 * kRowBytes + koff[kk]);
+      }
+    };
+    auto fire = [&](auto t_c) __attribute__((always_inline)) {
+      constexpr int t = decltype(t_c)::value;
+      if constexpr (t < 16) {
+        constexpr int sub = t >> 3, ks = (t >> 2) & 1, dt = t & 3;
+        if constexpr (dt < kDT) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ops[t], pop[sub][ks], acc[dt], 0, 0, 0);
+      } else {
+        constexpr int u = t - 16, kk = u >> 1, sub = u & 1;
+        if constexpr (kk < kKK) {
+          if constexpr (kk == 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
+          }
+          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ops[t], qop[kk], s[sub], 0, 0, 0);
         }
       }
+    };
+    static_for<kAhead>([&](auto d_c) __attribute__((always_inline)) {
+      constexpr int t = T0 + decltype(d_c)::value;
+      if constexpr (t < T1) fetch(std::integral_constant<int, t>{});
+    });
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<32>([&](auto t_c) __attribute__((always_inline)) {
+      constexpr int t = decltype(t_c)::value;
+      if constexpr (t >= T0 && t < T1) {
+        if constexpr (t + kAhead < T1) fetch(std::integral_constant<int, t + kAhead>{});
+        fire(t_c);
+        piece(std::integral_constant<int, (t - T0) * 32 / (T1 - T0)>{}, std::integral_constant<int, (t + 1 - T0) * 32 / (T1 - T0)>{});
+        __builtin_amdgcn_sched_barrier(0);           // the source order of the steps is the schedule
+      }
+    });
+  };
+  constexpr std::integral_constant<int, 0> c0{};
+  // ---- vector phase: online softmax of block blk.  Register i of s[sub] is token
+  // blk*64 + sub*32 + (i/8)*16 + h2*8 + (i%8) of row n32.  Scores stay unscaled in s; the scale (and,
+  // for FP8, the K scale of the token's page) is folded into the exponent with one fused
+  // multiply-add per element: p = 2^(s * sc - m).
+  auto softmax = [&](int blk) __attribute__((always_inline)) {
+    float sc[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) sc[p] = ksc_cur[p];
+    if (!positive_scale) {                             // rare: scale the scores themselves instead
+#pragma unroll
+      for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[sub][i] *= sc[sub * 2 + (i >> 3)];
+#pragma unroll
+      for (int p = 0; p < 4; ++p) sc[p] = 1.f;
     }
+    const int tok0 = blk * kBlockTokens;
+    if (tok0 + kBlockTokens - 1 > wave_min_pos) {      // causal edge or ragged end inside this block
+#pragma unroll
+      for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int tok = tok0 + sub * 32 + (i >> 3) * 16 + h2 * 8 + (i & 7);
+          if (tok > my_pos) s[sub][i] = -INFINITY;
+        }
+    }
+    // sc > 0 here, so the row maximum can be taken on the unscaled scores of each page
+    float pm[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int sub = p >> 1, o = (p & 1) * 8;
+      float x = fmaxf(fmaxf(s[sub][o], s[sub][o + 1]), s[sub][o + 2]);
+      x = fmaxf(fmaxf(x, s[sub][o + 3]), s[sub][o + 4]);
+      x = fmaxf(fmaxf(x, s[sub][o + 5]), s[sub][o + 6]);
+      pm[p] = fmaxf(x, s[sub][o + 7]);
+    }
+    float mloc;
+    if (FP8) mloc = fmaxf(fmaxf(pm[0] * sc[0], pm[1] * sc[1]), fmaxf(pm[2] * sc[2], pm[3] * sc[3]));
+    else mloc = fmaxf(fmaxf(pm[0], pm[1]), fmaxf(pm[2], pm[3])) * sc[0];
+    const float mx = xor32_max(mloc);
+    // The reference maximum only moves when a row's scores exceed it by more than 2^kSlack: until
+    // then p may be as large as 2^kSlack, which float sums and bf16 P hold without loss, and the
+    // accumulators are left alone.
+    const bool bump = mx > m_run + kSlack;             // also true for the first live block (-inf)
+    const float m_new = bump ? mx : m_run;
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;   // rows that see nothing yet
+    if (__builtin_amdgcn_ballot_w64(bump)) {
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
+      m_run = m_new;
+    }
+    float psum[2] = {0.f, 0.f};
+#pragma unroll
+    for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int p4 = sub * 2 + (i >> 3);
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[p4], -m_safe));
+        psum[sub & 1] += p;
+        pop[sub][i >> 3][i & 7] = (__bf16)(FP8 ? p * vsc_cur[p4] : p);
+      }
+    l_run += psum[0] + psum[1];
+#if PP_PIN
+#pragma unroll
+    for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        uintx4 t = __builtin_bit_cast(uintx4, pop[sub][ks]);
+        asm volatile("" : "+v"(t));
+        pop[sub][ks] = __builtin_bit_cast(bf16x8, t);
+      }
+#endif
   };
 
-  // ---- main loop: block j sits in LDS buffer j & 1; its global loads were issued two iterations
-  // before it is consumed and land in register slot j & 1 in between
+  // Two phases per block, a matrix phase (O += V P of the previous block, then S = K Q^T of this
+  // one) and a vector phase (softmax of this block, plus the workgroup's staging traffic), each
+  // closed by a workgroup barrier.  The trailing half of the waves entered the sequence one barrier
+  // late, so on every SIMD one wave is in its matrix phase while the other is in its vector phase
+  // and the two pipelines run side by side instead of taking turns.  K block i and V block i - 1 are
+  // read in phases 2i and 2i + 1 (leading, trailing half).
+  //   FP8:  unit i is written to LDS during those same two phases, into the other buffers, from
+  //         registers loaded two blocks earlier.
+  //   bf16: unit i is in flight from HBM from the matrix phase of block i - 1 on and must have
+  //         landed when phase 2i + 2 starts; every wave waits for its own loads at the end of its
+  //         matrix phase of block i.
+#if PP_TIME
+  long long t_acc[4] = {0, 0, 0, 0};   // matrix phase, its barrier wait, vector phase, its barrier wait
+  long long t_last = __builtin_amdgcn_s_memtime();
+#define BARRIER_T(k) do { __builtin_amdgcn_sched_barrier(0); { long long t = __builtin_amdgcn_s_memtime(); t_acc[k] += t - t_last; t_last = t; } \
+    BARRIER_RAW(); { long long t = __builtin_amdgcn_s_memtime(); t_acc[k + 1] += t - t_last; t_last = t; } __builtin_amdgcn_sched_barrier(0); } while (0)
+#else
+#define BARRIER_T(k) PHASE_END()
+#endif
+  // FP8: LDS writes must be complete, so the usual fence + barrier.  bf16: a bare barrier; the loads
+  // in flight must stay in flight across it, and a fence would wait for them.
+#define BARRIER_RAW() do { if (FP8) __syncthreads(); else asm volatile("s_barrier" ::: "memory"); } while (0)
+#define PHASE_END() do { __builtin_amdgcn_sched_barrier(0); BARRIER_RAW(); __builtin_amdgcn_sched_barrier(0); } while (0)
   constexpr std::integral_constant<int, 0> even{};
   constexpr std::integral_constant<int, 1> odd{};
-  // (block indices past the end are clamped: the redundant copy lands in the buffer nobody reads)
-  const int last_blk = n_blocks - 1;
-  issue(0, even);
-  issue(min(1, last_blk), odd);
-  commit(0, even);
-  __syncthreads();
-  for (int blk = 0; blk < n_blocks; blk += 2) {
-    issue(min(blk + 2, last_blk), even);
-    compute(blk, even);
-    commit(min(blk + 1, last_blk), odd);
-    __syncthreads();
-    if (blk + 1 < n_blocks) {
-      issue(min(blk + 3, last_blk), odd);
-      compute(blk + 1, odd);
-      commit(min(blk + 2, last_blk), even);
-      __syncthreads();
+  constexpr std::integral_constant<int, 16> c16{};
+  constexpr std::integral_constant<int, 32> c32{};
+  // All staging work is done by the wave that is in its matrix phase: that wave issues few
+  // instructions (32 MFMAs, 48 LDS reads), while the vector phase is bound by instruction issue.
+  // Page ids run ahead of the tile loads by one matrix phase, so that no load ever waits for an
+  // address: hist[0], hist[1] = this wave's page ids of blocks U + 1 and U, U being the unit it
+  // issues in its next matrix phase (U = block + 2 through registers, block + 1 direct).
+  constexpr int kLead = FP8 ? 2 : 1;
+  int hist[2][kLoads];
+  {
+    int h0[kLoads], h1[kLoads], h2[kLoads], h3[kLoads];
+    fetch_pids(0, h0); fetch_pids(1, h1); fetch_pids(2, h2); fetch_pids(3, h3);
+    fetch_spids(0);
+    load_scales(ksc_cur, vsc_cur);
+    fetch_spids(1);
+    if constexpr (FP8) {
+      uintx4 k0[kLoads];
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j)
+        if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
+          const TileAddr ka = tile_addr(a.k_pages, 0, 0, h0, j);
+          k0[j] = *(const uintx4*)(ka.base + ka.off);
+        }
+      issue(0, h1, h0, even);
+      issue(1, h2, h1, odd);
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j)
+        if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) put(k_lds[0] + woff[j][0], k0[j]);
+    } else {
+      dma_k(0, h0);
+      dma_k(1, h1); dma_v(0, h0);                    // unit 0
+      DMA_WAIT(2 * kLoads);                          // K block 0 has landed
+    }
+    PHASE_END();
+    if (grp == 1) PHASE_END();                       // the trailing half starts one phase late
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      hist[0][j] = FP8 ? h3[j] : h2[j];
+      hist[1][j] = FP8 ? h2[j] : h1[j];
     }
   }
+  // Staging share of the matrix phase of block i, cut into pieces; piece `pos` runs when the
+  // phase's schedule position passes pos.  Scalar loads come last: while one is in flight, any
+  // wait for an LDS read would have to drain the whole queue.
+  float ksc_nxt[4], vsc_nxt[4];
+  auto stage = [&](int i, auto slot_c, auto p0_c, auto p1_c) __attribute__((always_inline)) {
+    constexpr int p0 = decltype(p0_c)::value, p1 = decltype(p1_c)::value;
+    auto at = [&](int pos) constexpr { return p0 <= pos && pos < p1; };
+    const int u = i + kLead;                         // the unit issued in this phase
+    if constexpr (FP8) {
+      constexpr int slot = decltype(slot_c)::value;
+      if constexpr (at(0)) {
+        if (i > 0) {
+#pragma unroll
+          for (int p = 0; p < 4; ++p) { ksc_cur[p] = ksc_nxt[p]; vsc_cur[p] = vsc_nxt[p]; }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j) {
+        const bool mine = kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens;
+        // unit i (K block i + 1, V block i) from registers to LDS, then the registers are reloaded
+        if (at(2 + 12 * j / kLoads) && mine) put(k_lds[(i + 1) & 1] + woff[j][0], kreg[slot][j]);
+        if (at(6 + 12 * j / kLoads) && mine) put(v_lds[i & 1] + woff[j][1], vreg[slot][j]);
+        if (at(14 + 8 * j / kLoads) && mine) {
+          const TileAddr ka = tile_addr(a.k_pages, 0, u + 1, hist[0], j);
+          kreg[slot][j] = *(const uintx4*)(ka.base + ka.off);
+        }
+        if (at(18 + 8 * j / kLoads) && mine) {
+          const TileAddr va = tile_addr(a.v_pages, 1, u, hist[1], j);
+          vreg[slot][j] = *(const uintx4*)(va.base + va.off);
+        }
+      }
+      if constexpr (at(31)) {
+        load_scales(ksc_nxt, vsc_nxt);               // block i + 1
+        fetch_spids(i + 2);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j) {
+        if (at(2 + 8 * j / kLoads))
+          dma(tile_addr(a.k_pages, 0, u + 1, hist[0], j), k_lds[0] + ((unsigned)(u + 1) % 3u) * kTileBytes + wave * 1024 + j * kThreads * 16);
+        if (at(10 + 8 * j / kLoads))
+          dma(tile_addr(a.v_pages, 1, u, hist[1], j), v_lds[0] + ((unsigned)u % 3u) * kTileBytes + wave * 1024 + j * kThreads * 16);
+      }
+      if constexpr (at(26)) DMA_WAIT(2 * kLoads);    // everything but the unit just issued has landed
+    }
+    if constexpr (at(31)) {
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j) hist[1][j] = hist[0][j];
+      fetch_pids(u + 2, hist[0]);
+    }
+  };
+  auto no_piece = [](auto, auto) {};
+#if PP_TIME
+  t_last = __builtin_amdgcn_s_memtime();
+#endif
+  // block 0 has no predecessor: scores only
+  __builtin_amdgcn_s_setprio(PP_PRIO);
+  matrix_phase(c16, c32, 0, 0, [&](auto p0, auto p1) __attribute__((always_inline)) { stage(0, even, p0, p1); });
+  __builtin_amdgcn_s_setprio(0);
+  BARRIER_T(0);
+  softmax(0);
+  BARRIER_T(2);
+  int kb = 1 % kRing, vb = 0;                        // ring slots of K block i and V block i - 1
+  for (int i = 1; i < n_blocks; i += 2) {
+    __builtin_amdgcn_s_setprio(PP_PRIO);
+    matrix_phase(c0, c32, kb, vb, [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i, odd, p0, p1); });
+    __builtin_amdgcn_s_setprio(0);
+    BARRIER_T(0);
+    softmax(i);
+    BARRIER_T(2);
+    vb = kb; kb = (kb + 1 == kRing) ? 0 : kb + 1;
+    if (i + 1 < n_blocks) {
+      __builtin_amdgcn_s_setprio(PP_PRIO);
+      matrix_phase(c0, c32, kb, vb, [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i + 1, even, p0, p1); });
+      __builtin_amdgcn_s_setprio(0);
+      BARRIER_T(0);
+      softmax(i + 1);
+      BARRIER_T(2);
+      vb = kb; kb = (kb + 1 == kRing) ? 0 : kb + 1;
+    }
+  }
+  __builtin_amdgcn_s_setprio(PP_PRIO);
+  matrix_phase(c0, c16, 0, vb, no_piece);
+  __builtin_amdgcn_s_setprio(0);
+  if (grp == 0) PHASE_END();
+  if constexpr (!FP8) DMA_WAIT(0);                   // nothing may still be landing in LDS when the workgroup retires
+#undef PHASE_END
+#undef BARRIER_RAW
+#undef BARRIER_T
+#undef DMA_WAIT
+#if PP_TIME
+  if (blockIdx.x == PP_TIME - 1 && lane == 0 && (wave == 0 || wave == 4)) {
+    long long* dbg = (long long*)(a.header + 32) + grp * 4;
+    for (int k = 0; k < 4; ++k) dbg[k] = t_acc[k];
+    a.header[48] = n_blocks;
+  }
+#endif
 
   // ---- normalise and store: lane (row n32, half h2) owns dims dt*32 + (i/4)*8 + h2*4 + i%4
   l_run = xor32_add(l_run);

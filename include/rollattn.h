@@ -65,7 +65,8 @@ typedef enum {
 typedef enum {
   ROLLATTN_OK = 0,
   ROLLATTN_EINVAL = -1,     /* null pointer, negative size, NULL descriptor            */
-  ROLLATTN_ESHAPE = -2,     /* Hq % Hkv != 0, unsupported head_dim or page_size        */
+  ROLLATTN_ESHAPE = -2,     /* Hq % Hkv != 0, unsupported head_dim or page_size,
+                               num_pages * Hkv >= 2^31                                 */
   ROLLATTN_EDTYPE = -3,     /* unsupported q/kv type pair, FP8 without scales          */
   ROLLATTN_EALIGN = -4,     /* a device pointer is not 16-byte aligned                 */
   ROLLATTN_EWORKSPACE = -5, /* workspace smaller than rollattn_workspace_bytes()       */

@@ -42,6 +42,7 @@ int check_desc(const rollattn_desc* d, bool need_scales = true) {
   if (d->num_q_heads < 1 || d->num_kv_heads < 1 || d->num_q_heads % d->num_kv_heads) return ROLLATTN_ESHAPE;
   if (d->head_dim != 64 && d->head_dim != 128) return ROLLATTN_ESHAPE;
   if (d->page_size != kPageSize) return ROLLATTN_ESHAPE;
+  if (d->num_pages * (int64_t)d->num_kv_heads > INT32_MAX) return ROLLATTN_ESHAPE;   // (page, head) tiles are counted in 32 bits
   const bool f32 = d->q_dtype == ROLLATTN_F32 && d->kv_dtype == ROLLATTN_F32;
   const bool bf = d->q_dtype == ROLLATTN_BF16 && (d->kv_dtype == ROLLATTN_BF16 || d->kv_dtype == ROLLATTN_FP8_E4M3);
   if (!f32 && !bf) return ROLLATTN_EDTYPE;

@@ -3,45 +3,29 @@
 //
 // One workgroup = 256 query rows of one (trajectory, KV head): a row is a (chunk token, query
 // head of the group) pair, token-major, so the G heads that share the KV head reuse every K/V
-// tile.  Eight waves of 32 rows each walk the visible KV range in 64-token blocks (four
-// pages) that the workgroup stages once through LDS (double buffered, global loads two
-// blocks ahead of the one being consumed).  FP8 pools are widened to bf16
-// while staging, so the tiles in LDS always hold bf16; page scales are applied in float to
-// S (K scale) and to P (V scale).  Per 32-token sub-block a wave computes
+// tile.  Eight waves of 32 rows each walk the visible KV range in 64-token blocks (four pages)
+// that the workgroup stages once in LDS, always as bf16: bf16 pools are copied from HBM into LDS
+// directly (no register stop, ring of three tiles per pool), FP8 pools pass through registers to
+// be widened (two tiles per pool, loads two blocks ahead); page scales are applied in float to S
+// (K scale) and to P (V scale).  Per block a wave computes
 //   S^T = K Q^T        tokens x rows, v_mfma_f32_32x32x16_bf16, K rows as A operand
 //   O^T += V^T P^T     dims x rows, V read transposed with ds_read_b64_tr_b16
 // The transposed products keep "row" on the lane axis in both accumulators: the softmax
 // state is one scalar per lane (shared by two lanes) and P goes from accumulator registers
 // straight into the B operand of the second product.
+//
+// Schedule.  A SIMD holds two of the workgroup's waves (w and w + 4).  Left alone they run in
+// step, both in their MFMAs and then both in their softmax, and the matrix and vector pipelines
+// take turns.  Here every block is cut into a matrix phase (the second product of the previous
+// block, then the first product of this one) and a vector phase (this block's softmax), each
+// closed by a workgroup barrier, and waves 4-7 enter the sequence one barrier late: on every SIMD
+// one wave feeds the matrix core while the other does the exponentials.  A wave in a phase has
+// no partner to hide its latencies, so the matrix phase reads its LDS operands several steps
+// ahead in a fixed source-order schedule, and it also carries all the staging work (addresses,
+// loads, FP8 widening), threaded between the MFMAs, because the vector phase is the one bound by
+// its own instruction stream.
 #include <type_traits>
 #include <utility>
-#ifndef PP_ORDER
-#define PP_ORDER 0
-#endif
-#ifndef PP_SALU
-#define PP_SALU 3
-#endif
-#ifndef PP_VALU
-#define PP_VALU 2
-#endif
-#ifndef PP_AHEAD
-#define PP_AHEAD 4
-#endif
-#ifndef PP_SCHED
-#define PP_SCHED 1
-#endif
-#ifndef PP_GRP
-#define PP_GRP 0
-#endif
-#ifndef PP_TIME
-#define PP_TIME 0
-#endif
-#ifndef PP_PIN
-#define PP_PIN 1
-#endif
-#ifndef PP_PRIO
-#define PP_PRIO 1
-#endif
 
 #include "rollattn_internal.h"
 
@@ -217,19 +201,28 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   // The 64 chunks a wave fetches with one instruction lie in one page, so its id is a scalar.
   // fetch_pids: the page ids behind this wave's kLoads loads of one block (block index clamped to
   // the last block, page index to the last live page).
-  int pj[kLoads];
+  int pj[kLoads], lim[kLoads];
+  const_i32_p table_j[kLoads];
 #pragma unroll
-  for (int j = 0; j < kLoads; ++j) pj[j] = ((j * kThreads + wave * 64) / kSrcChunks) / kPageSize;
+  for (int j = 0; j < kLoads; ++j) {
+    pj[j] = ((j * kThreads + wave * 64) / kSrcChunks) / kPageSize;
+    lim[j] = live_pages - 1 - pj[j];                  // first page of a block >= lim: the load touches the last live page
+    table_j[j] = table + pj[j];
+  }
   auto fetch_pids = [&](int blk, int* dst) __attribute__((always_inline)) {
+    const int b4 = min(blk, last_blk) * kPagesPerBlock;
 #pragma unroll
-    for (int j = 0; j < kLoads; ++j) dst[j] = table[min(min(blk, last_blk) * kPagesPerBlock + pj[j], live_pages - 1)];
+    for (int j = 0; j < kLoads; ++j) dst[j] = table_j[j][min(b4, lim[j])];
+  };
+  // byte offset of the (page, KV head) tile in either pool
+  auto tile_off_of = [&](int pid) __attribute__((always_inline)) -> size_t {
+    return (size_t)(unsigned int)(pid * hkv + g) * tile_stride;
   };
   // one wave-wide 16-byte load of block blk: scalar tile base, per-lane offset
   struct TileAddr { const unsigned char* base; unsigned int off; };
-  auto tile_addr = [&](const void* pool, int pool_i, int blk, const int* pids, int j) __attribute__((always_inline)) -> TileAddr {
-    const int pg = min(blk, last_blk) * kPagesPerBlock + pj[j];
-    const size_t tile_off = ((size_t)pids[j] * hkv + g) * tile_stride;     // scalar
-    return TileAddr{(const unsigned char*)pool + tile_off, (pg >= live_pages - 1) ? goff_last[j][pool_i] : goff[j][pool_i]};
+  auto tile_addr = [&](const void* pool, int pool_i, int blk, size_t toff, int j) __attribute__((always_inline)) -> TileAddr {
+    const int b4 = min(blk, last_blk) * kPagesPerBlock;
+    return TileAddr{(const unsigned char*)pool + toff, (b4 >= lim[j]) ? goff_last[j][pool_i] : goff[j][pool_i]};
   };
   // -- register path (FP8)
   uintx4 kreg[2][kLoads], vreg[2][kLoads];   // two units in flight
@@ -238,30 +231,18 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
       if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
-        const TileAddr ka = tile_addr(a.k_pages, 0, u + 1, pk, j), va = tile_addr(a.v_pages, 1, u, pv, j);
+        const TileAddr ka = tile_addr(a.k_pages, 0, u + 1, tile_off_of(pk[j]), j), va = tile_addr(a.v_pages, 1, u, tile_off_of(pv[j]), j);
         kreg[slot][j] = *(const uintx4*)(ka.base + ka.off);
         vreg[slot][j] = *(const uintx4*)(va.base + va.off);
       }
     }
   };
-  auto put = [&](unsigned char* dst, const uintx4 raw) __attribute__((always_inline)) {
+  auto put = [&](unsigned char* tile, int off, const uintx4 raw) __attribute__((always_inline)) {
     // the two 16-byte halves of the widened chunk sit in chunks 2c and 2c + 1: 16 bytes apart after the swizzle
     uintx4 lo, hi;
     fp8x16_to_bf16(raw, lo, hi);
-    *(uintx4*)dst = lo;
-    *(uintx4*)((unsigned char*)((uintptr_t)dst ^ 16)) = hi;
-  };
-  auto commit = [&](int u, auto slot_c) __attribute__((always_inline)) {
-    constexpr int slot = decltype(slot_c)::value;
-    unsigned char* kdst = k_lds[(u + 1) & 1];
-    unsigned char* vdst = v_lds[u & 1];
-#pragma unroll
-    for (int j = 0; j < kLoads; ++j) {
-      if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
-        put(kdst + woff[j][0], kreg[slot][j]);
-        put(vdst + woff[j][1], vreg[slot][j]);
-      }
-    }
+    *(uintx4*)(tile + off) = lo;
+    *(uintx4*)(tile + (off ^ 16)) = hi;
   };
   // -- direct path (bf16): HBM -> LDS without a register stop.  Lane l's 16 bytes land at
   // M0 + 16 l.  The compiler does not see these loads: completion is awaited by count below, and
@@ -270,16 +251,6 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   auto dma = [&](const TileAddr& t, unsigned char* lds_dst) __attribute__((always_inline)) {
     const unsigned int m0 = __builtin_amdgcn_readfirstlane((unsigned int)(uintptr_t)lds_dst);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(t.off), "s"(t.base));
-  };
-  auto dma_k = [&](int blk, const int* pids) __attribute__((always_inline)) {
-    unsigned char* dst = k_lds[0] + ((unsigned)blk % 3u) * kTileBytes + wave * 1024;
-#pragma unroll
-    for (int j = 0; j < kLoads; ++j) dma(tile_addr(a.k_pages, 0, blk, pids, j), dst + j * kThreads * 16);
-  };
-  auto dma_v = [&](int blk, const int* pids) __attribute__((always_inline)) {
-    unsigned char* dst = v_lds[0] + ((unsigned)blk % 3u) * kTileBytes + wave * 1024;
-#pragma unroll
-    for (int j = 0; j < kLoads; ++j) dma(tile_addr(a.v_pages, 1, blk, pids, j), dst + j * kThreads * 16);
   };
 #define DMA_WAIT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n))
 
@@ -326,16 +297,16 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   bf16x8 pop[kSubs][2];     // its probabilities, as B operands of the second product
 
   // ---- matrix phase: up to 32 MFMA steps, O^T += V^T P^T for the previous block (steps 0-15, V buffer
-  // vb) and S^T = K Q^T for this one (steps 16-31, K buffer kb).  Every step needs one 32x16 operand
+  // at vbo) and S^T = K Q^T for this one (steps 16-31, K buffer at kbo).  Every step needs one 32x16 operand
   // from LDS; the reads run kAhead steps in front of the MFMAs that consume them, because during
   // this phase no second wave hides the LDS latency.  After step t the caller's piece(p0, p1) runs
   // with [p0, p1) the slice of 32 schedule positions that the step covers: that is where the
   // staging work of the phase is threaded between the MFMAs.
-  constexpr int kAhead = PP_AHEAD;
-  auto matrix_phase = [&](auto first_c, auto last_c, int kb, int vb, auto&& piece) __attribute__((always_inline)) {
+  constexpr int kAhead = 4;
+  auto matrix_phase = [&](auto first_c, auto last_c, int kbo, int vbo, auto&& piece) __attribute__((always_inline)) {
     constexpr int T0 = decltype(first_c)::value, T1 = decltype(last_c)::value;
-    const unsigned char* kbuf = k_lds[0] + kb * kTileBytes;
-    const unsigned char* vbuf = v_lds[0] + vb * kTileBytes;
+    const unsigned char* kbuf = k_lds[0] + kbo;    // byte offsets of the ring slots
+    const unsigned char* vbuf = v_lds[0] + vbo;
     typedef __attribute__((address_space(3))) shortx4 lds_s4;
     bf16x8 ops[32];
     auto fetch = [&](auto t_c) __attribute__((always_inline)) {
@@ -414,27 +385,46 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
           if (tok > my_pos) s[sub][i] = -INFINITY;
         }
     }
-    // sc > 0 here, so the row maximum can be taken on the unscaled scores of each page
-    float pm[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int sub = p >> 1, o = (p & 1) * 8;
-      float x = fmaxf(fmaxf(s[sub][o], s[sub][o + 1]), s[sub][o + 2]);
-      x = fmaxf(fmaxf(x, s[sub][o + 3]), s[sub][o + 4]);
-      x = fmaxf(fmaxf(x, s[sub][o + 5]), s[sub][o + 6]);
-      pm[p] = fmaxf(x, s[sub][o + 7]);
-    }
+    // sc > 0 here, so the row maximum can be taken on the unscaled scores (of each page, where the
+    // pages have scales of their own)
     float mloc;
-    if (FP8) mloc = fmaxf(fmaxf(pm[0] * sc[0], pm[1] * sc[1]), fmaxf(pm[2] * sc[2], pm[3] * sc[3]));
-    else mloc = fmaxf(fmaxf(pm[0], pm[1]), fmaxf(pm[2], pm[3])) * sc[0];
-    const float mx = xor32_max(mloc);
+    if (FP8) {
+      float pm[4];
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int sub = p >> 1, o = (p & 1) * 8;
+        float x = fmaxf(fmaxf(s[sub][o], s[sub][o + 1]), s[sub][o + 2]);
+        x = fmaxf(fmaxf(x, s[sub][o + 3]), s[sub][o + 4]);
+        x = fmaxf(fmaxf(x, s[sub][o + 5]), s[sub][o + 6]);
+        pm[p] = fmaxf(x, s[sub][o + 7]);
+      }
+      mloc = fmaxf(fmaxf(pm[0] * sc[0], pm[1] * sc[1]), fmaxf(pm[2] * sc[2], pm[3] * sc[3]));
+    } else {
+      float x[kSubs];
+#pragma unroll
+      for (int sub = 0; sub < kSubs; ++sub) {          // three-input maxima, one chain per sub-block
+        x[sub] = fmaxf(fmaxf(s[sub][0], s[sub][1]), s[sub][2]);
+#pragma unroll
+        for (int i = 3; i < 15; i += 2) x[sub] = fmaxf(fmaxf(x[sub], s[sub][i]), s[sub][i + 1]);
+      }
+      mloc = fmaxf(fmaxf(x[0], s[0][15]), fmaxf(x[1], s[1][15])) * sc[0];
+    }
     // The reference maximum only moves when a row's scores exceed it by more than 2^kSlack: until
     // then p may be as large as 2^kSlack, which float sums and bf16 P hold without loss, and the
-    // accumulators are left alone.
+    // accumulators are left alone.  The exponentials are therefore started against the old
+    // reference, before the block's maximum is known (it takes a chain of dependent steps that would
+    // otherwise leave this wave idle), and are only redone in the blocks that do move the reference.
+    const float m_old = (m_run == -INFINITY) ? 0.f : m_run;
+    float p[kSubs][16];
+#pragma unroll
+    for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) p[sub][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[sub * 2 + (i >> 3)], -m_old));
+    const float mx = xor32_max(mloc);
     const bool bump = mx > m_run + kSlack;             // also true for the first live block (-inf)
-    const float m_new = bump ? mx : m_run;
-    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;   // rows that see nothing yet
     if (__builtin_amdgcn_ballot_w64(bump)) {
+      const float m_new = bump ? mx : m_run;
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;   // rows that see nothing yet
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
       l_run *= alpha;
 #pragma unroll
@@ -442,19 +432,22 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
       m_run = m_new;
+#pragma unroll
+      for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) p[sub][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[sub * 2 + (i >> 3)], -m_safe));
     }
-    float psum[2] = {0.f, 0.f};
+    float psum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int p4 = sub * 2 + (i >> 3);
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[p4], -m_safe));
-        psum[sub & 1] += p;
-        pop[sub][i >> 3][i & 7] = (__bf16)(FP8 ? p * vsc_cur[p4] : p);
+        psum[p4] += p[sub][i];
+        pop[sub][i >> 3][i & 7] = (__bf16)(FP8 ? p[sub][i] * vsc_cur[p4] : p[sub][i]);
       }
-    l_run += psum[0] + psum[1];
-#if PP_PIN
+    l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
+    // the probabilities are finished here, in this phase, not wherever the compiler would like to sink them
 #pragma unroll
     for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
@@ -463,7 +456,6 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         asm volatile("" : "+v"(t));
         pop[sub][ks] = __builtin_bit_cast(bf16x8, t);
       }
-#endif
   };
 
   // Two phases per block, a matrix phase (O += V P of the previous block, then S = K Q^T of this
@@ -477,14 +469,6 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   //   bf16: unit i is in flight from HBM from the matrix phase of block i - 1 on and must have
   //         landed when phase 2i + 2 starts; every wave waits for its own loads at the end of its
   //         matrix phase of block i.
-#if PP_TIME
-  long long t_acc[4] = {0, 0, 0, 0};   // matrix phase, its barrier wait, vector phase, its barrier wait
-  long long t_last = __builtin_amdgcn_s_memtime();
-#define BARRIER_T(k) do { __builtin_amdgcn_sched_barrier(0); { long long t = __builtin_amdgcn_s_memtime(); t_acc[k] += t - t_last; t_last = t; } \
-    BARRIER_RAW(); { long long t = __builtin_amdgcn_s_memtime(); t_acc[k + 1] += t - t_last; t_last = t; } __builtin_amdgcn_sched_barrier(0); } while (0)
-#else
-#define BARRIER_T(k) PHASE_END()
-#endif
   // FP8: LDS writes must be complete, so the usual fence + barrier.  bf16: a bare barrier; the loads
   // in flight must stay in flight across it, and a fence would wait for them.
 #define BARRIER_RAW() do { if (FP8) __syncthreads(); else asm volatile("s_barrier" ::: "memory"); } while (0)
@@ -498,8 +482,16 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   // Page ids run ahead of the tile loads by one matrix phase, so that no load ever waits for an
   // address: hist[0], hist[1] = this wave's page ids of blocks U + 1 and U, U being the unit it
   // issues in its next matrix phase (U = block + 2 through registers, block + 1 direct).
-  constexpr int kLead = FP8 ? 2 : 1;
-  int hist[2][kLoads];
+  constexpr int kLead = FP8 ? 2 : kRing - 2;
+  size_t toff[2][kLoads];      // tile offsets of this wave's loads of K block U + 1 and V block U
+  int pid_new[kLoads];         // page ids of K block U + 1, not yet turned into an offset
+  // ko[d]: byte offset of the ring slot of block i + d (i = the block whose matrix phase comes
+  // next); block i - 1 shares the slot of block i + kRing - 1.
+  int ko[kRing];
+#pragma unroll
+  for (int d = 0; d < kRing; ++d) ko[d] = d * kTileBytes;
+  float ksc_nxt[4], vsc_nxt[4];
+  unsigned int kraw[4], vraw[4];
   {
     int h0[kLoads], h1[kLoads], h2[kLoads], h3[kLoads];
     fetch_pids(0, h0); fetch_pids(1, h1); fetch_pids(2, h2); fetch_pids(3, h3);
@@ -511,124 +503,145 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #pragma unroll
       for (int j = 0; j < kLoads; ++j)
         if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
-          const TileAddr ka = tile_addr(a.k_pages, 0, 0, h0, j);
+          const TileAddr ka = tile_addr(a.k_pages, 0, 0, tile_off_of(h0[j]), j);
           k0[j] = *(const uintx4*)(ka.base + ka.off);
         }
       issue(0, h1, h0, even);
       issue(1, h2, h1, odd);
 #pragma unroll
       for (int j = 0; j < kLoads; ++j)
-        if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) put(k_lds[0] + woff[j][0], k0[j]);
+        if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) put(k_lds[0], woff[j][0], k0[j]);
     } else {
-      dma_k(0, h0);
-      dma_k(1, h1); dma_v(0, h0);                    // unit 0
-      DMA_WAIT(2 * kLoads);                          // K block 0 has landed
+      const int* hh[4] = {h0, h1, h2, h3};
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j)
+        dma(tile_addr(a.k_pages, 0, 0, tile_off_of(h0[j]), j), k_lds[0] + wave * 1024 + j * kThreads * 16);
+#pragma unroll
+      for (int u0 = 0; u0 < kLead; ++u0)             // units 0 .. kLead - 1
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) {
+          dma(tile_addr(a.k_pages, 0, u0 + 1, tile_off_of(hh[u0 + 1][j]), j), k_lds[0] + (u0 + 1) * kTileBytes + wave * 1024 + j * kThreads * 16);
+          dma(tile_addr(a.v_pages, 1, u0, tile_off_of(hh[u0][j]), j), v_lds[0] + u0 * kTileBytes + wave * 1024 + j * kThreads * 16);
+        }
+      DMA_WAIT(kLead * 2 * kLoads);                  // K block 0 has landed
     }
     PHASE_END();
     if (grp == 1) PHASE_END();                       // the trailing half starts one phase late
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
-      hist[0][j] = FP8 ? h3[j] : h2[j];
-      hist[1][j] = FP8 ? h2[j] : h1[j];
+      pid_new[j] = kLead == 2 ? h3[j] : h2[j];
+      toff[0][j] = tile_off_of(kLead == 2 ? h2[j] : h1[j]);
     }
   }
   // Staging share of the matrix phase of block i, cut into pieces; piece `pos` runs when the
-  // phase's schedule position passes pos.  Scalar loads come last: while one is in flight, any
-  // wait for an LDS read would have to drain the whole queue.
-  float ksc_nxt[4], vsc_nxt[4];
+  // phase's schedule position passes pos.
   auto stage = [&](int i, auto slot_c, auto p0_c, auto p1_c) __attribute__((always_inline)) {
     constexpr int p0 = decltype(p0_c)::value, p1 = decltype(p1_c)::value;
     auto at = [&](int pos) constexpr { return p0 <= pos && pos < p1; };
     const int u = i + kLead;                         // the unit issued in this phase
-    if constexpr (FP8) {
-      constexpr int slot = decltype(slot_c)::value;
-      if constexpr (at(0)) {
-        if (i > 0) {
+    if constexpr (at(0)) {
 #pragma unroll
-          for (int p = 0; p < 4; ++p) { ksc_cur[p] = ksc_nxt[p]; vsc_cur[p] = vsc_nxt[p]; }
+      for (int j = 0; j < kLoads; ++j) { toff[1][j] = toff[0][j]; toff[0][j] = tile_off_of(pid_new[j]); }
+      if (FP8 && i > 0) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) { ksc_cur[p] = ksc_nxt[p]; vsc_cur[p] = vsc_nxt[p]; }
+      }
+      // Scalar loads for the next round go out at once: the wait for the first operands of this
+      // phase then covers them as well, and later waits can count LDS reads again.
+      fetch_pids(u + 2, pid_new);
+      if constexpr (FP8) {
+        // scales of block i + 1: eight loads in one statement, so that each keeps a register of its
+        // own (the compiler would recycle one register and wait after every load)
+        asm volatile(
+            "s_load_dword %0, %8, %10\n\ts_load_dword %1, %8, %11\n\ts_load_dword %2, %8, %12\n\ts_load_dword %3, %8, %13\n\t"
+            "s_load_dword %4, %9, %10\n\ts_load_dword %5, %9, %11\n\ts_load_dword %6, %9, %12\n\ts_load_dword %7, %9, %13"
+            : "=&s"(kraw[0]), "=&s"(kraw[1]), "=&s"(kraw[2]), "=&s"(kraw[3]), "=&s"(vraw[0]), "=&s"(vraw[1]), "=&s"(vraw[2]), "=&s"(vraw[3])
+            : "s"(a.k_scale), "s"(a.v_scale), "s"((unsigned)spid[0] * 4u), "s"((unsigned)spid[1] * 4u), "s"((unsigned)spid[2] * 4u),
+              "s"((unsigned)spid[3] * 4u));
+        fetch_spids(i + 2);
+      }
+    }
+    if constexpr (at(1)) {                           // ... and must have arrived here, not wherever they are used next
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j) asm volatile("" : "+s"(pid_new[j]));
+      if constexpr (FP8) {
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+s"(kraw[0]), "+s"(kraw[1]), "+s"(kraw[2]), "+s"(kraw[3]), "+s"(vraw[0]), "+s"(vraw[1]), "+s"(vraw[2]), "+s"(vraw[3]));
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          asm volatile("" : "+s"(spid[p]));
+          ksc_nxt[p] = __uint_as_float(kraw[p]) * a.scale_log2;
+          vsc_nxt[p] = __uint_as_float(vraw[p]);
         }
       }
+    }
+    if constexpr (FP8) {
+      constexpr int slot = decltype(slot_c)::value;
 #pragma unroll
       for (int j = 0; j < kLoads; ++j) {
         const bool mine = kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens;
         // unit i (K block i + 1, V block i) from registers to LDS, then the registers are reloaded
-        if (at(2 + 12 * j / kLoads) && mine) put(k_lds[(i + 1) & 1] + woff[j][0], kreg[slot][j]);
-        if (at(6 + 12 * j / kLoads) && mine) put(v_lds[i & 1] + woff[j][1], vreg[slot][j]);
+        if (at(2 + 12 * j / kLoads) && mine) put(k_lds[0] + ko[1], woff[j][0], kreg[slot][j]);
+        if (at(6 + 12 * j / kLoads) && mine) put(v_lds[0] + ko[0], woff[j][1], vreg[slot][j]);
         if (at(14 + 8 * j / kLoads) && mine) {
-          const TileAddr ka = tile_addr(a.k_pages, 0, u + 1, hist[0], j);
+          const TileAddr ka = tile_addr(a.k_pages, 0, u + 1, toff[0][j], j);
           kreg[slot][j] = *(const uintx4*)(ka.base + ka.off);
         }
         if (at(18 + 8 * j / kLoads) && mine) {
-          const TileAddr va = tile_addr(a.v_pages, 1, u, hist[1], j);
+          const TileAddr va = tile_addr(a.v_pages, 1, u, toff[1][j], j);
           vreg[slot][j] = *(const uintx4*)(va.base + va.off);
         }
-      }
-      if constexpr (at(31)) {
-        load_scales(ksc_nxt, vsc_nxt);               // block i + 1
-        fetch_spids(i + 2);
       }
     } else {
 #pragma unroll
       for (int j = 0; j < kLoads; ++j) {
-        if (at(2 + 8 * j / kLoads))
-          dma(tile_addr(a.k_pages, 0, u + 1, hist[0], j), k_lds[0] + ((unsigned)(u + 1) % 3u) * kTileBytes + wave * 1024 + j * kThreads * 16);
-        if (at(10 + 8 * j / kLoads))
-          dma(tile_addr(a.v_pages, 1, u, hist[1], j), v_lds[0] + ((unsigned)u % 3u) * kTileBytes + wave * 1024 + j * kThreads * 16);
+        if (at(2 + 8 * j / kLoads)) dma(tile_addr(a.k_pages, 0, u + 1, toff[0][j], j), k_lds[0] + ko[kRing - 1] + wave * 1024 + j * kThreads * 16);
+        if (at(10 + 8 * j / kLoads)) dma(tile_addr(a.v_pages, 1, u, toff[1][j], j), v_lds[0] + ko[kRing - 2] + wave * 1024 + j * kThreads * 16);
       }
-      if constexpr (at(26)) DMA_WAIT(2 * kLoads);    // everything but the unit just issued has landed
-    }
-    if constexpr (at(31)) {
-#pragma unroll
-      for (int j = 0; j < kLoads; ++j) hist[1][j] = hist[0][j];
-      fetch_pids(u + 2, hist[0]);
+      if constexpr (at(26)) DMA_WAIT(kLead * 2 * kLoads);   // everything but the kLead newest units has landed
     }
   };
   auto no_piece = [](auto, auto) {};
-#if PP_TIME
-  t_last = __builtin_amdgcn_s_memtime();
-#endif
+  auto next_block = [&]() __attribute__((always_inline)) {
+    const int t = ko[0];
+#pragma unroll
+    for (int d = 0; d + 1 < kRing; ++d) ko[d] = ko[d + 1];
+    ko[kRing - 1] = t;
+  };
   // block 0 has no predecessor: scores only
-  __builtin_amdgcn_s_setprio(PP_PRIO);
-  matrix_phase(c16, c32, 0, 0, [&](auto p0, auto p1) __attribute__((always_inline)) { stage(0, even, p0, p1); });
+  __builtin_amdgcn_s_setprio(1);
+  matrix_phase(c16, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(0, even, p0, p1); });
   __builtin_amdgcn_s_setprio(0);
-  BARRIER_T(0);
+  PHASE_END();
   softmax(0);
-  BARRIER_T(2);
-  int kb = 1 % kRing, vb = 0;                        // ring slots of K block i and V block i - 1
+  PHASE_END();
+  next_block();
   for (int i = 1; i < n_blocks; i += 2) {
-    __builtin_amdgcn_s_setprio(PP_PRIO);
-    matrix_phase(c0, c32, kb, vb, [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i, odd, p0, p1); });
+    __builtin_amdgcn_s_setprio(1);
+    matrix_phase(c0, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i, odd, p0, p1); });
     __builtin_amdgcn_s_setprio(0);
-    BARRIER_T(0);
+    PHASE_END();
     softmax(i);
-    BARRIER_T(2);
-    vb = kb; kb = (kb + 1 == kRing) ? 0 : kb + 1;
+    PHASE_END();
+    next_block();
     if (i + 1 < n_blocks) {
-      __builtin_amdgcn_s_setprio(PP_PRIO);
-      matrix_phase(c0, c32, kb, vb, [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i + 1, even, p0, p1); });
+      __builtin_amdgcn_s_setprio(1);
+      matrix_phase(c0, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i + 1, even, p0, p1); });
       __builtin_amdgcn_s_setprio(0);
-      BARRIER_T(0);
+      PHASE_END();
       softmax(i + 1);
-      BARRIER_T(2);
-      vb = kb; kb = (kb + 1 == kRing) ? 0 : kb + 1;
+      PHASE_END();
+      next_block();
     }
   }
-  __builtin_amdgcn_s_setprio(PP_PRIO);
-  matrix_phase(c0, c16, 0, vb, no_piece);
+  __builtin_amdgcn_s_setprio(1);
+  matrix_phase(c0, c16, 0, ko[kRing - 1], no_piece);
   __builtin_amdgcn_s_setprio(0);
   if (grp == 0) PHASE_END();
   if constexpr (!FP8) DMA_WAIT(0);                   // nothing may still be landing in LDS when the workgroup retires
 #undef PHASE_END
 #undef BARRIER_RAW
-#undef BARRIER_T
 #undef DMA_WAIT
-#if PP_TIME
-  if (blockIdx.x == PP_TIME - 1 && lane == 0 && (wave == 0 || wave == 4)) {
-    long long* dbg = (long long*)(a.header + 32) + grp * 4;
-    for (int k = 0; k < 4; ++k) dbg[k] = t_acc[k];
-    a.header[48] = n_blocks;
-  }
-#endif
 
   // ---- normalise and store: lane (row n32, half h2) owns dims dt*32 + (i/4)*8 + h2*4 + i%4
   l_run = xor32_add(l_run);

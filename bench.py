@@ -6,8 +6,9 @@
 A step is one pass of the whole attention path over one synthetic batch that is already
 resident in HBM: the device-side plan, the main kernel and (decode) the split-K merge.  The
 headline workload is the mid-size bf16 decode batch; the long-tail decode, the
-observation-append batch and the mixed FP8 rollout step are timed after it and reported in
-the same JSON line under "workloads".  Every figure is throughput on ALGORITHMIC bytes /
+observation-append batch, the mixed FP8 rollout step and the KV-recomputation prefill (append
+with an empty prefix over whole histories) are timed after it and reported in the same JSON
+line under "workloads".  Every figure is throughput on ALGORITHMIC bytes /
 flops (K and V of each KV head once per call, live page-table entries, page scales, Q in,
 O out; 4*Hq*D flops per attended pair), never on what the kernels happen to move.
 
@@ -38,7 +39,7 @@ def _parts(batch, c):
     """(kind, sub-batch) legs of one step of configuration c."""
     if c in (2, 3):
         return [("decode", batch)]
-    if c == 4:
+    if c in (4, "recompute"):
         return [("append", batch)]
     return [("decode", batch.select(batch.decode_rows())), ("append", batch.select(batch.append_rows()))]
 
@@ -150,7 +151,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4 or c5 (or `copy`: 1 GiB copy for counter calibration)")
+    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4, c5 or recompute (or `copy`: 1 GiB copy for counter calibration)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -176,12 +177,15 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "copy", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": max(1, a.steps)}))
         return
-    selected = [int(a.only.lstrip("c"))] if a.only else [HEADLINE, 3, 4, 5]
+    if a.only:
+        selected = ["recompute"] if a.only == "recompute" else [int(a.only.lstrip("c"))]
+    else:
+        selected = [HEADLINE, 3, 4, 5, "recompute"]
     reports = {}
     headline = None
     cpu = None
     for c in selected:
-        w = W.CONFIGS[c]
+        w = W.RECOMPUTE if c == "recompute" else W.CONFIGS[c]
         batch = W.build(w, dev)
         small = W.algorithmic_work(w, batch.ctx_lens_host, batch.q_lens_host)["kv_bytes"] < 2e9
         legs = [Leg(kind, bb, B, W, n_pools=3 if small else 1) for kind, bb in _parts(batch, c)]

@@ -99,7 +99,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
 // Append work list: each chunk cut into tiles of tile_tokens query tokens.  A tile's cost grows
 // with its trajectory's context, and workgroups are dispatched in list order, so (for batches that
 // fit the ranking in LDS) trajectories are listed longest context first: the long tiles start
-// early and the short ones fill the tail.
+// early and the short ones fill the tail.  For the same reason a chunk's tiles are listed last
+// tile first.
 constexpr int kRankBatch = 4096;
 __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
     const int32_t* __restrict__ q_lens, const int32_t* __restrict__ ctx_lens, int32_t batch, int32_t tile_tokens,
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
     for (int s = 0; s < count; ++s) {
       if (first + s < cap) {
         tile_b[first + s] = b;
-        tile_q0[first + s] = s * tile_tokens;
+        tile_q0[first + s] = (count - 1 - s) * tile_tokens;   // a chunk's last tile sees the most context
       }
     }
     running += tile_total;

@@ -75,6 +75,12 @@ CONFIGS = {
 }
 
 
+# KV recomputation after a weight update (Section 6.2, protocol step 5): every in-flight trajectory's
+# whole history is prefilled again, i.e. an append step with an empty prefix.  Lengths as in config 2.
+RECOMPUTE = Workload("recompute_bf16_b64", 64, 32, 8, 128, "bf16", "bf16", ("const", 0),
+                     qlen=("loguniform", 512, 8192), ctx_is_prefix=True, seed=BASE_SEED + 6)
+
+
 def scaled(w: Workload, *, batch=None, ctx=None, qlen=None, append_rows=None, name=None, seed=None,
            num_q_heads=None, num_kv_heads=None, head_dim=None, q_dtype=None, kv_dtype=None) -> Workload:
     """A reduced (or otherwise altered) copy of a configuration for parity tests."""

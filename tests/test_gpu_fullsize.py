@@ -89,3 +89,29 @@ def test_workspace_is_sized_from_the_descriptor_alone():
     b.ctx_lens_host = short
     b.ctx_lens = torch.from_numpy(short.astype(np.int32)).to(DEV)
     check(gpu_decode(b, workspace=ws), oracle_decode(b), "bf16", "same workspace, short rows")
+
+
+def test_recompute_prefill_full_size():
+    # KV recomputation after a weight update (Section 6.2, protocol step 5): append with an empty
+    # prefix over whole histories, in the launch configuration the bench times.  Row i of a chunk
+    # equals a decode step at context i + 1: that is what the oracle computes for the sampled rows
+    # (tile edges, block edges, first and last rows of the shortest, the median and the longest
+    # history, and seeded random ones).
+    from oracle import attention as O
+    w = W.RECOMPUTE
+    b = W.build(w, DEV)
+    out = gpu_append(b)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    rng = np.random.default_rng(7)
+    offs = np.concatenate([[0], np.cumsum(b.q_lens_host)])
+    order = np.argsort(b.ctx_lens_host)
+    q, kp, vp, pt = (W.raw_numpy(t) for t in (b.q, b.k_pages, b.v_pages, b.page_table))
+    qs, tables, lens, idx = [], [], [], []
+    for traj in (int(order[0]), int(order[len(order) // 2]), int(order[-1])):
+        n = int(b.q_lens_host[traj])
+        for i in sorted(set([0, 1, 63, 64, 255, 256, n // 2, n - 2, n - 1] + rng.integers(0, n, 6).tolist())):
+            if 0 <= i < n:
+                qs.append(q[offs[traj] + i]); tables.append(pt[traj]); lens.append(i + 1); idx.append(int(offs[traj] + i))
+    ref = O.attn_decode(np.stack(qs), kp, vp, np.stack(tables), np.asarray(lens), sm_scale=w.sm_scale, q_dtype="bf16", kv_dtype="bf16")
+    check(out[torch.tensor(idx, device=DEV)], ref, "bf16", "recompute prefill, sampled rows")

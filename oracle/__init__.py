@@ -16,4 +16,8 @@ for this step, so the result is the textbook softmax-attention definition and ev
 pin in the CPU tests comes from mathematics (closed forms, invariants, brute force,
 a library routine on the special case it covers), not from the paper:
 "parity unpinned by the paper" for all functions here in that sense.
+
+`kv_write` defines the step that precedes attention, the scatter of the new tokens' K/V
+rows into the paged cache (with the E4M3 page-scale rule of FP8 pools); its header states
+the reading taken and its pins.
 """

@@ -22,7 +22,8 @@
  * Memory.  All array arguments are DEVICE pointers unless marked "host".  The caller
  * owns every buffer; the library allocates nothing, frees nothing and keeps no state
  * between calls apart from the optional profiling events below.  Inputs are only
- * read; `out` and `workspace` are the only memory written.  Every device pointer must
+ * read; `out` and `workspace` are the only memory written (kv_write writes the pools and the
+ * page scales instead).  Every device pointer must
  * be 16-byte aligned.  Layouts are dense row-major:
  *   q, out        [rows][Hq][D]                 rows = B (decode) or total_q (append)
  *   k_pages,
@@ -111,6 +112,30 @@ int attn_append(const rollattn_desc *desc, const void *q_chunk, const int32_t *q
                 const int32_t *q_offsets, int32_t total_q, int32_t max_q_len, const void *k_pages,
                 const void *v_pages, const int32_t *page_table, const int32_t *ctx_lens, void *out,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* KV write, the step before either attention call: every turn of a trajectory appends tokens to its
+ * history (Section 2.1), whose KV stays cached (Section 7.1), so the K and V rows of the new tokens
+ * (one per trajectory before attn_decode, the chunk before attn_append) are put into the pages.
+ * ctx_lens INCLUDES the new tokens, as in attn_append: new row i of trajectory b goes to position
+ * L_b - n_b + i, page page_table[b][pos / 16], slot pos % 16, for every KV head.
+ *   k_new, v_new [total_q][Hkv][D], elements of desc->q_dtype (F32 or BF16), rows packed in batch
+ *   order as q_chunk is; q_offsets [B+1] their exclusive scan; max_q_len >= max n_b (host).
+ *   Pools of the source type take the rows bit for bit.  FP8 pools (BF16 source) hold E4M3 codes
+ *   times one float scale per physical page and pool, k_scale / v_scale [num_pages] (device, read
+ *   and written here; desc->k_scale / v_scale are ignored).  Per page that receives new rows in
+ *   slots [s0, s1): amax = largest |x| of those rows over all heads; s0 == 0: scale = amax / 448,
+ *   or 1 if amax == 0; otherwise scale = max(old scale, amax / 448), and if that raised it the
+ *   codes in slots [0, s0) are replaced by enc(dec(code) * old / scale); new codes are
+ *   enc(x / scale).  Every product and quotient is one float32 operation, enc rounds to nearest
+ *   even after clamping to [-448, 448]: the result is defined bit for bit.
+ * A page written here must belong to exactly one trajectory of the batch (shared prefix pages are
+ * complete and are never written again); inputs must be finite; B <= 65535.  Pool slots and scales
+ * of pages that receive nothing are left untouched.  No workspace; total_q == 0 succeeds without a
+ * launch. */
+int kv_write(const rollattn_desc *desc, const void *k_new, const void *v_new, const int32_t *q_lens,
+             const int32_t *q_offsets, int32_t total_q, int32_t max_q_len, void *k_pages, void *v_pages,
+             const int32_t *page_table, const int32_t *ctx_lens, float *k_scale, float *v_scale,
+             void *hip_stream);
 
 /* Bytes of workspace either call needs for this descriptor; total_q is the number of
  * query rows (B for decode).  Depends on the descriptor only, never on device data.

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "librollattn.so")
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
 EXPORTS = (
-    "attn_decode", "attn_append", "rollattn_workspace_bytes", "rollattn_debug_gather",
+    "attn_decode", "attn_append", "kv_write", "rollattn_workspace_bytes", "rollattn_debug_gather",
     "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan",
     "rollattn_profile_enable", "rollattn_profile_read", "rollattn_status_string",
     "rollattn_last_hip_error", "rollattn_version",
@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         l.attn_decode.restype = ctypes.c_int
         l.attn_append.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         l.attn_append.restype = ctypes.c_int
+        l.kv_write.argtypes = [dp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        l.kv_write.restype = ctypes.c_int
         l.rollattn_workspace_bytes.argtypes = [dp, i32]
         l.rollattn_workspace_bytes.restype = ctypes.c_size_t
         l.rollattn_debug_gather.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp]
@@ -169,6 +171,19 @@ def attn_append(q_chunk, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_le
     if rc:
         raise RollattnError(rc, "attn_append")
     return out
+
+
+def kv_write(k_new, v_new, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, *, max_q_len,
+             k_scale=None, v_scale=None, stream=None) -> None:
+    """Puts the new tokens' K / V rows (packed by trajectory, [total_q, Hkv, D]) into the pools in place;
+    FP8 pools also get their page scales updated in place."""
+    _check_contig(k_new, v_new, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, k_scale, v_scale)
+    desc = make_desc(k_new, k_pages, page_table, sm_scale=1.0)
+    rc = lib().kv_write(ctypes.byref(desc), _ptr(k_new), _ptr(v_new), _ptr(q_lens), _ptr(q_offsets), int(k_new.shape[0]),
+                        int(max_q_len), _ptr(k_pages), _ptr(v_pages), _ptr(page_table), _ptr(ctx_lens), _ptr(k_scale),
+                        _ptr(v_scale), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "kv_write")
 
 
 def debug_gather(pages, page_table, ctx_lens, b, kv_head, length, stream=None) -> torch.Tensor:

@@ -340,6 +340,27 @@ int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q
   return ROLLATTN_OK;
 }
 
+int kv_write(const rollattn_desc* desc, const void* k_new, const void* v_new, const int32_t* q_lens,
+             const int32_t* q_offsets, int32_t total_q, int32_t max_q_len, void* k_pages, void* v_pages,
+             const int32_t* page_table, const int32_t* ctx_lens, float* k_scale, float* v_scale, void* hip_stream) {
+  int rc = check_desc(desc, /*need_scales=*/false);
+  if (rc) return rc;
+  if (total_q < 0 || max_q_len < 0) return ROLLATTN_EINVAL;
+  if (desc->batch == 0 || total_q == 0) return ROLLATTN_OK;
+  const bool fp8 = desc->kv_dtype == ROLLATTN_FP8_E4M3;
+  if (!k_new || !v_new || !q_lens || !q_offsets || !k_pages || !v_pages || !page_table || !ctx_lens) return ROLLATTN_EINVAL;
+  if (fp8 && (!k_scale || !v_scale)) return ROLLATTN_EDTYPE;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q_lens) || !aligned16(q_offsets) || !aligned16(k_pages) ||
+      !aligned16(v_pages) || !aligned16(page_table) || !aligned16(ctx_lens) || (fp8 && (!aligned16(k_scale) || !aligned16(v_scale))))
+    return ROLLATTN_EALIGN;
+  if (desc->batch > 65535) return ROLLATTN_ESHAPE;     // one grid row per trajectory
+  const hipError_t e = launch_kv_write(k_new, v_new, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, k_scale,
+                                       v_scale, desc->batch, desc->num_kv_heads, desc->max_pages_per_seq, max_q_len,
+                                       desc->head_dim, desc->q_dtype == ROLLATTN_F32 ? 4 : 2, fp8, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail_hip(e);
+  return ROLLATTN_OK;
+}
+
 int rollattn_debug_gather(const rollattn_desc* desc, const void* pages, const int32_t* page_table,
                           const int32_t* ctx_lens, int32_t b, int32_t kv_head, void* dst, void* hip_stream) {
   int rc = check_desc(desc, /*need_scales=*/false);

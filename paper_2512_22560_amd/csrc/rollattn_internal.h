@@ -85,6 +85,10 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, int head_dim, bool fp8, int g
 hipError_t launch_combine(const DecodeArgs& a, int head_dim, bool out_bf16, hipStream_t s);
 hipError_t launch_append_mfma(const AppendArgs& a, int head_dim, bool fp8, int grid, hipStream_t s);
 hipError_t launch_append_f32(const AppendArgs& a, int head_dim, int grid, hipStream_t s);
+hipError_t launch_kv_write(const void* k_new, const void* v_new, const int32_t* q_lens, const int32_t* q_offsets,
+                           void* k_pages, void* v_pages, const int32_t* page_table, const int32_t* ctx_lens,
+                           float* k_scale, float* v_scale, int32_t batch, int32_t hkv, int32_t max_pages,
+                           int32_t max_q_len, int head_dim, int src_bytes, bool fp8, hipStream_t s);
 hipError_t launch_gather(const void* pages, const int32_t* page_table, const int32_t* ctx_lens, int32_t b,
                          int32_t kv_head, int32_t hkv, int32_t max_pages, int32_t row_bytes, void* dst,
                          hipStream_t s);

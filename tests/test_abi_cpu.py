@@ -24,7 +24,7 @@ def _desc(**kw):
 def test_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "rollattn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(attn_\w+|rollattn_\w+)\s*\(", text))
+    declared = set(re.findall(r"\b(attn_\w+|kv_\w+|rollattn_\w+)\s*\(", text))
     declared -= {"rollattn_desc", "rollattn_status", "rollattn_dtype"}
     assert declared == set(B.EXPORTS)
     lib = B.lib()
@@ -52,6 +52,16 @@ def test_descriptor_errors_are_reported_before_any_launch():
     assert lib.attn_append(ctypes.byref(_desc()), fake, fake, fake, 0, 0, fake, fake, fake, fake, fake, fake, 0, None) == 0
     assert lib.attn_append(ctypes.byref(_desc()), fake, fake, fake, -1, 0, fake, fake, fake, fake, fake, fake, 0, None) == -1
     assert lib.attn_append(ctypes.byref(_desc()), fake, fake, fake, 8, 2, fake, fake, fake, fake, fake, fake, 16, None) == -5
+    def write(d, total_q=4, k_new=fake, ks=fake, max_q=1):
+        return lib.kv_write(ctypes.byref(d), k_new, fake, fake, fake, total_q, max_q, fake, fake, fake, fake, ks, fake, None)
+    assert write(_desc(), total_q=0) == 0                          # nothing to write: success, no launch
+    assert write(_desc(), total_q=-1) == -1
+    assert write(_desc(head_dim=96)) == -2
+    assert write(_desc(), k_new=None) == -1
+    assert write(_desc(), k_new=ctypes.c_void_p(0x1004)) == -4
+    assert write(_desc(q_dtype=B.BF16, kv_dtype=B.FP8_E4M3, head_dim=128), ks=None) == -3   # FP8 pools need scale arrays
+    assert write(_desc(q_dtype=B.F32, kv_dtype=B.FP8_E4M3)) == -3
+    assert write(_desc(batch=70000)) == -2
     for code in range(-6, 1):
         assert lib.rollattn_status_string(code)
     assert lib.rollattn_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 4) == 0

@@ -7,8 +7,8 @@ A step is one pass of the whole attention path over one synthetic batch that is 
 resident in HBM: the device-side plan, the main kernel and (decode) the split-K merge.  The
 headline workload is the mid-size bf16 decode batch; the long-tail decode, the
 observation-append batch, the mixed FP8 rollout step and the KV-recomputation prefill (append
-with an empty prefix over whole histories) are timed after it and reported in the same JSON
-line under "workloads".  Every figure is throughput on ALGORITHMIC bytes /
+with an empty prefix over whole histories) and the KV write of the append chunks (bf16 and FP8
+pools) are timed after it and reported in the same JSON line under "workloads".  Every figure is throughput on ALGORITHMIC bytes /
 flops (K and V of each KV head once per call, live page-table entries, page scales, Q in,
 O out; 4*Hq*D flops per attended pair), never on what the kernels happen to move.
 
@@ -41,6 +41,10 @@ def _parts(batch, c):
         return [("decode", batch)]
     if c in (4, "recompute"):
         return [("append", batch)]
+    if c == "kv_write_c4":
+        return [("kv_write", batch)]
+    if c == "kv_write_c5":
+        return [("kv_write", batch.select(batch.append_rows()))]
     return [("decode", batch.select(batch.decode_rows())), ("append", batch.select(batch.append_rows()))]
 
 
@@ -57,6 +61,19 @@ class Leg:
         self.ws = B.alloc_workspace(desc, bb.total_q, bb.q.device)
         self.out = torch.empty_like(bb.q)
         self.max_q = int(max(1, bb.q_lens_host.max(initial=1)))
+        if kind == "kv_write":
+            # new K / V rows for the chunk region of the cache; unit-scale values as everywhere else
+            g = torch.Generator(device=bb.q.device).manual_seed(w.seed)
+            shape = (bb.total_q, w.num_kv_heads, w.head_dim)
+            self.k_new = torch.randn(shape, generator=g, device=bb.q.device, dtype=torch.float32).to(bb.q.dtype)
+            self.v_new = torch.randn(shape, generator=g, device=bb.q.device, dtype=torch.float32).to(bb.q.dtype)
+            kvb = {"f32": 4, "bf16": 2, "fp8_e4m3": 1}[w.kv_dtype]
+            srcb = {"f32": 4, "bf16": 2}[w.q_dtype]
+            first = bb.ctx_lens_host - bb.q_lens_host
+            pages = np.where(bb.q_lens_host > 0, (bb.ctx_lens_host + 15) // 16 - first // 16, 0).sum()
+            rows = int(bb.q_lens_host.sum()) * w.num_kv_heads * w.head_dim
+            # rows read once and written once per pool, one table entry per touched page, FP8: its two scales read and written
+            self.work = {"bytes": int(2 * rows * (srcb + kvb) + 4 * pages + (16 * pages if w.kv_dtype == "fp8_e4m3" else 0)), "flops": 0}
         # Rotating copies of the pools keep the 256 MB last-level cache from serving a small KV set.
         self.pools = [(bb.k_pages, bb.v_pages)]
         for _ in range(n_pools - 1):
@@ -67,7 +84,10 @@ class Leg:
         bb, w, B = self.bb, self.w, self.B
         k, v = self.pools[self.i % len(self.pools)]
         self.i += 1
-        if self.kind == "decode":
+        if self.kind == "kv_write":
+            B.kv_write(self.k_new, self.v_new, bb.q_lens, bb.q_offsets, k, v, bb.page_table, bb.ctx_lens, max_q_len=self.max_q,
+                       k_scale=bb.k_scale, v_scale=bb.v_scale)
+        elif self.kind == "decode":
             B.attn_decode(bb.q, k, v, bb.page_table, bb.ctx_lens, sm_scale=w.sm_scale, k_scale=bb.k_scale,
                           v_scale=bb.v_scale, out=self.out, workspace=self.ws)
         else:
@@ -103,9 +123,9 @@ def time_legs(legs, steps, warmup, B):
 def leg_report(leg, kms):
     avg = float(np.mean(kms))
     work = leg.work
-    if leg.kind == "decode":
+    if leg.kind in ("decode", "kv_write"):
         ach = work["bytes"] / avg / 1e6
-        return {"kind": "decode", "bound": "hbm", "kernel_ms_avg": avg, "kernel_ms_min": float(np.min(kms)),
+        return {"kind": leg.kind, "bound": "hbm", "kernel_ms_avg": avg, "kernel_ms_min": float(np.min(kms)),
                 "algorithmic_bytes": work["bytes"], "achieved": ach, "unit": "GB/s", "peak": HBM_PEAK_GBS,
                 "frac": ach / HBM_PEAK_GBS}
     ach = work["flops"] / avg / 1e9
@@ -151,7 +171,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4, c5 or recompute (or `copy`: 1 GiB copy for counter calibration)")
+    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4, c5, recompute, kv_write_c4 or kv_write_c5 (or `copy`: 1 GiB copy for counter calibration)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -177,15 +197,16 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "copy", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": max(1, a.steps)}))
         return
+    extra = {"recompute": W.RECOMPUTE, "kv_write_c4": W.CONFIGS[4], "kv_write_c5": W.CONFIGS[5]}
     if a.only:
-        selected = ["recompute"] if a.only == "recompute" else [int(a.only.lstrip("c"))]
+        selected = [a.only] if a.only in extra else [int(a.only.lstrip("c"))]
     else:
-        selected = [HEADLINE, 3, 4, 5, "recompute"]
+        selected = [HEADLINE, 3, 4, 5, "recompute", "kv_write_c4", "kv_write_c5"]
     reports = {}
     headline = None
     cpu = None
     for c in selected:
-        w = W.RECOMPUTE if c == "recompute" else W.CONFIGS[c]
+        w = extra[c] if c in extra else W.CONFIGS[c]
         batch = W.build(w, dev)
         small = W.algorithmic_work(w, batch.ctx_lens_host, batch.q_lens_host)["kv_bytes"] < 2e9
         legs = [Leg(kind, bb, B, W, n_pools=3 if small else 1) for kind, bb in _parts(batch, c)]
@@ -194,7 +215,7 @@ def main():
         rep = {"ms_per_step": ms, "steps": steps, "legs": [leg_report(l, k) for l, k in zip(legs, kms)],
                "batch": w.batch, "heads": [w.num_q_heads, w.num_kv_heads, w.head_dim], "kv_dtype": w.kv_dtype,
                "tokens": int(batch.ctx_lens_host.sum()), "query_rows": int(batch.q_lens_host.sum())}
-        reports[w.name] = rep
+        reports[c if str(c).startswith("kv_write") else w.name] = rep
         if c == selected[0]:
             headline = (w, rep, legs)
             if not a.no_cpu and c in (2, 3):

@@ -173,7 +173,7 @@ int32_t rollattn_plan_workers(const rollattn_desc *desc);
 int rollattn_debug_read_plan(const rollattn_desc *desc, const void *workspace, int32_t *per_out,
                              int32_t *total_out, int32_t *starts_out, void *hip_stream);
 
-/* Optional per-kernel timing.  While enabled, attn_decode / attn_append bracket their
+/* Optional per-kernel timing.  While enabled, attn_decode / attn_append / kv_write bracket their
  * main kernel (not the planning or merge kernels) with HIP events on the call's stream;
  * rollattn_profile_read synchronises those events and returns up to `cap` durations in
  * milliseconds, oldest first, then forgets them.  At most 1024 launches are kept. */

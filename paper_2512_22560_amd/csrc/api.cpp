@@ -354,9 +354,12 @@ int kv_write(const rollattn_desc* desc, const void* k_new, const void* v_new, co
       !aligned16(v_pages) || !aligned16(page_table) || !aligned16(ctx_lens) || (fp8 && (!aligned16(k_scale) || !aligned16(v_scale))))
     return ROLLATTN_EALIGN;
   if (desc->batch > 65535) return ROLLATTN_ESHAPE;     // one grid row per trajectory
+  hipStream_t s = (hipStream_t)hip_stream;
+  ProfileScope prof(s);
   const hipError_t e = launch_kv_write(k_new, v_new, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, k_scale,
                                        v_scale, desc->batch, desc->num_kv_heads, desc->max_pages_per_seq, max_q_len,
-                                       desc->head_dim, desc->q_dtype == ROLLATTN_F32 ? 4 : 2, fp8, (hipStream_t)hip_stream);
+                                       desc->head_dim, desc->q_dtype == ROLLATTN_F32 ? 4 : 2, fp8, s);
+  prof.stop();
   if (e != hipSuccess) return fail_hip(e);
   return ROLLATTN_OK;
 }

@@ -107,12 +107,29 @@ __global__ __launch_bounds__(kThreads) void kv_write_kernel(const KvWriteArgs a)
       static_assert(!FP8 || SRC_BYTES == 2, "FP8 pools are written from bf16 rows");
       float* scale = pool ? a.v_scale : a.k_scale;
       unsigned char* tile = pages + (size_t)phys * hkv * kPageSize * D;
+      // The rows are needed twice, for the maximum and for the codes: a page's worth (up to kKeep
+      // chunks per thread, which covers 8 KV heads at D = 128) stays in registers in between.
+      constexpr int kKeep = 8;
+      const bool keep = chunks <= kKeep * kThreads;
+      uintx4 held[kKeep];
       float amax = 0.f;
-      for (int c = threadIdx.x; c < chunks; c += kThreads) {
-        float x[8];
-        bf16x8_to_float(*(const uintx4*)(src + (size_t)c * 16), x);
+      if (keep) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(x[i]));
+        for (int i = 0; i < kKeep; ++i) {
+          const int c = threadIdx.x + i * kThreads;
+          held[i] = c < chunks ? *(const uintx4*)(src + (size_t)c * 16) : uintx4{0, 0, 0, 0};
+          float x[8];
+          bf16x8_to_float(held[i], x);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(x[e]));
+        }
+      } else {
+        for (int c = threadIdx.x; c < chunks; c += kThreads) {
+          float x[8];
+          bf16x8_to_float(*(const uintx4*)(src + (size_t)c * 16), x);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(x[i]));
+        }
       }
       amax = block_max(amax, red);
       const float need = amax / kE4m3Max;
@@ -143,14 +160,23 @@ __global__ __launch_bounds__(kThreads) void kv_write_kernel(const KvWriteArgs a)
           }
         }
       }
-      for (int c = threadIdx.x; c < chunks; c += kThreads) {
+      auto emit = [&](int c, const uintx4 raw) {
         const int col = c % kChunksPerRow, rh = c / kChunksPerRow;
         const int h = rh % hkv, slot = rh / hkv;
         float x[8];
-        bf16x8_to_float(*(const uintx4*)(src + (size_t)c * 16), x);
+        bf16x8_to_float(raw, x);
 #pragma unroll
         for (int i = 0; i < 8; ++i) x[i] = x[i] / s_new;
         *(uintx2*)(tile + (size_t)(h * kPageSize + s0 + slot) * D + col * 8) = encode8(x);
+      };
+      if (keep) {
+#pragma unroll
+        for (int i = 0; i < kKeep; ++i) {
+          const int c = threadIdx.x + i * kThreads;
+          if (c < chunks) emit(c, held[i]);
+        }
+      } else {
+        for (int c = threadIdx.x; c < chunks; c += kThreads) emit(c, *(const uintx4*)(src + (size_t)c * 16));
       }
       __syncthreads();                                   // every read of the old scale is done
       if (threadIdx.x == 0) scale[phys] = s_new;

@@ -33,6 +33,11 @@ METRIC = "decode-attn achieved HBM GB/s (% of peak) + append TFLOP/s, ragged pag
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 HEADLINE = 2
+# HBM bytes per launch of the headline workload's main kernel, from hardware counters (FETCH_SIZE and
+# WRITE_SIZE, each scaled by its reading on a copy of known size; profiles/decode_mfma_c2_decode_bf16_b64.md
+# has the commands and the raw readings).  Valid for the decode kernel as committed with that profile:
+# set to None when the kernel changes, until the counters have been taken again.
+HEADLINE_TRAFFIC_BYTES = {"decode_mfma_kernel": 814_241_126 + 5_120_725}
 
 
 def _parts(batch, c):
@@ -238,7 +243,9 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads,
                    "head_dim": w.head_dim, "page_size": 16, "kv_dtype": w.kv_dtype, "tokens": rep["tokens"]},
         "roofline": {"bound": lead["bound"], "achieved": lead["achieved"], "peak": lead["peak"], "unit": lead["unit"],
-                     "frac": lead["frac"], "traffic": None, "kernel": "decode_mfma_kernel" if lead["kind"] == "decode" else "append_mfma_kernel",
+                     "frac": lead["frac"],
+                     "traffic": HEADLINE_TRAFFIC_BYTES.get("decode_mfma_kernel") if (lead["kind"] == "decode" and w is W.CONFIGS[HEADLINE]) else None,
+                     "kernel": "decode_mfma_kernel" if lead["kind"] == "decode" else "append_mfma_kernel",
                      "kernel_ms_avg": lead["kernel_ms_avg"]},
         "cpu_baseline": cpu,
         "workloads": reports,

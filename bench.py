@@ -114,6 +114,37 @@ def time_legs(legs, steps, warmup, B):
             leg.step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+    # the same step captured once in a HIP graph and replayed (every entry point plans on the device and
+    # neither allocates nor synchronises): one graph holds as many steps as there are rotating pools
+    per_graph = max(len(leg.pools) for leg in legs)
+    graph_ms = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for leg in legs:
+                leg.step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for leg in legs:
+            leg.i = 0
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(per_graph):
+                for leg in legs:
+                    leg.step()
+        torch.cuda.synchronize()
+        replays = max(1, steps // per_graph)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / (replays * per_graph) * 1e3
+        del graph
+    except Exception as e:      # reported, never fatal: the eager figures above are the contract
+        print(f"bench.py: graph replay skipped: {e}", file=sys.stderr)
     kernel_ms = []
     for leg in legs:
         B.profile_enable(True)
@@ -122,7 +153,7 @@ def time_legs(legs, steps, warmup, B):
         torch.cuda.synchronize()
         kernel_ms.append(B.profile_read())
         B.profile_enable(False)
-    return ms_per_step, kernel_ms
+    return ms_per_step, kernel_ms, graph_ms
 
 
 def leg_report(leg, kms):
@@ -216,8 +247,8 @@ def main():
         small = W.algorithmic_work(w, batch.ctx_lens_host, batch.q_lens_host)["kv_bytes"] < 2e9
         legs = [Leg(kind, bb, B, W, n_pools=3 if small else 1) for kind, bb in _parts(batch, c)]
         steps = a.steps if c == selected[0] else max(5, min(a.steps, 20))
-        ms, kms = time_legs(legs, steps, a.warmup, B)
-        rep = {"ms_per_step": ms, "steps": steps, "legs": [leg_report(l, k) for l, k in zip(legs, kms)],
+        ms, kms, gms = time_legs(legs, steps, a.warmup, B)
+        rep = {"ms_per_step": ms, "graph_ms_per_step": gms, "steps": steps, "legs": [leg_report(l, k) for l, k in zip(legs, kms)],
                "batch": w.batch, "heads": [w.num_q_heads, w.num_kv_heads, w.head_dim], "kv_dtype": w.kv_dtype,
                "tokens": int(batch.ctx_lens_host.sum()), "query_rows": int(batch.q_lens_host.sum())}
         reports[c if str(c).startswith("kv_write") else w.name] = rep

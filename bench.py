@@ -8,7 +8,9 @@ resident in HBM: the device-side plan, the main kernel and (decode) the split-K 
 headline workload is the mid-size bf16 decode batch; the long-tail decode, the
 observation-append batch, the mixed FP8 rollout step and the KV-recomputation prefill (append
 with an empty prefix over whole histories) and the KV write of the append chunks (bf16 and FP8
-pools) are timed after it and reported in the same JSON line under "workloads".  Every figure is throughput on ALGORITHMIC bytes /
+pools) and the decode step of grouped rollouts that share an 8k prompt (with the prompt read once
+per group, and plain decode on the same aliased tables for comparison) are timed after it and
+reported in the same JSON line under "workloads".  Every figure is throughput on ALGORITHMIC bytes /
 flops (K and V of each KV head once per call, live page-table entries, page scales, Q in,
 O out; 4*Hq*D flops per attended pair), never on what the kernels happen to move.
 
@@ -19,6 +21,7 @@ float64 oracle, untuned, on the host cores of the same box, on the same bytes.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -40,7 +43,7 @@ HEADLINE = 2
 HEADLINE_TRAFFIC_BYTES = {"decode_mfma_kernel": 814_241_126 + 5_120_725}
 
 
-def _parts(batch, c):
+def _parts(batch, c, W):
     """(kind, sub-batch) legs of one step of configuration c."""
     if c in (2, 3):
         return [("decode", batch)]
@@ -48,6 +51,10 @@ def _parts(batch, c):
         return [("append", batch)]
     if c == "kv_write_c4":
         return [("kv_write", batch)]
+    if c in ("shared_prompt", "shared_prompt_plain"):
+        n_groups = batch.workload.batch // W.SHARED_PROMPT_GROUP
+        aliased = W.alias_shared_prefix(batch, W.SHARED_PROMPT_GROUP, np.full(n_groups, W.SHARED_PROMPT_TOKENS))
+        return [("decode_shared" if c == "shared_prompt" else "decode_aliased", aliased)]
     if c == "kv_write_c5":
         return [("kv_write", batch.select(batch.append_rows()))]
     return [("decode", batch.select(batch.decode_rows())), ("append", batch.select(batch.append_rows()))]
@@ -59,6 +66,7 @@ class Leg:
     def __init__(self, kind, bb, B, W, n_pools=1):
         import torch
         self.kind, self.bb, self.B = kind, bb, B
+        self.group_size = W.SHARED_PROMPT_GROUP
         w = bb.workload
         self.w = w
         self.work = W.algorithmic_work(w, bb.ctx_lens_host, bb.q_lens_host)
@@ -66,6 +74,19 @@ class Leg:
         self.ws = B.alloc_workspace(desc, bb.total_q, bb.q.device)
         self.out = torch.empty_like(bb.q)
         self.max_q = int(max(1, bb.q_lens_host.max(initial=1)))
+        if kind == "decode_shared":
+            n_groups = w.batch // W.SHARED_PROMPT_GROUP
+            self.shared_lens = torch.full((n_groups,), W.SHARED_PROMPT_TOKENS, dtype=torch.int32, device=bb.q.device)
+            self.ws = torch.empty(int(B.lib().rollattn_shared_workspace_bytes(ctypes.byref(desc), W.SHARED_PROMPT_GROUP)),
+                                  dtype=torch.uint8, device=bb.q.device)
+        if kind in ("decode_shared", "decode_aliased"):
+            # bytes that have to move when every physical page is read once: the prompts per group, the rest per trajectory
+            kvb = {"f32": 4, "bf16": 2, "fp8_e4m3": 1}[w.kv_dtype]
+            n_groups = w.batch // W.SHARED_PROMPT_GROUP
+            uniq = n_groups * W.SHARED_PROMPT_TOKENS + int((bb.ctx_lens_host - W.SHARED_PROMPT_TOKENS).sum())
+            pages = n_groups * (W.SHARED_PROMPT_TOKENS // 16) + int(((bb.ctx_lens_host - W.SHARED_PROMPT_TOKENS + 15) // 16).sum())
+            self.work = {"bytes": int(2 * w.num_kv_heads * w.head_dim * kvb * uniq + pages * (4 + (8 if kvb == 1 else 0))
+                                      + 2 * bb.total_q * w.num_q_heads * w.head_dim * 2), "flops": 0}
         if kind == "kv_write":
             # new K / V rows for the chunk region of the cache; unit-scale values as everywhere else
             g = torch.Generator(device=bb.q.device).manual_seed(w.seed)
@@ -89,10 +110,14 @@ class Leg:
         bb, w, B = self.bb, self.w, self.B
         k, v = self.pools[self.i % len(self.pools)]
         self.i += 1
-        if self.kind == "kv_write":
+        if self.kind == "decode_shared":
+            B.attn_decode_shared(bb.q, k, v, bb.page_table, bb.ctx_lens, group_size=self.group_size,
+                                 shared_lens=self.shared_lens, sm_scale=w.sm_scale, k_scale=bb.k_scale, v_scale=bb.v_scale,
+                                 out=self.out, workspace=self.ws)
+        elif self.kind == "kv_write":
             B.kv_write(self.k_new, self.v_new, bb.q_lens, bb.q_offsets, k, v, bb.page_table, bb.ctx_lens, max_q_len=self.max_q,
                        k_scale=bb.k_scale, v_scale=bb.v_scale)
-        elif self.kind == "decode":
+        elif self.kind in ("decode", "decode_aliased"):
             B.attn_decode(bb.q, k, v, bb.page_table, bb.ctx_lens, sm_scale=w.sm_scale, k_scale=bb.k_scale,
                           v_scale=bb.v_scale, out=self.out, workspace=self.ws)
         else:
@@ -157,9 +182,11 @@ def time_legs(legs, steps, warmup, B):
 
 
 def leg_report(leg, kms):
+    if leg.kind == "decode_shared":           # two main kernels per step (shared half, private half): report their sum
+        kms = np.asarray(kms)[: len(kms) // 2 * 2].reshape(-1, 2).sum(axis=1)
     avg = float(np.mean(kms))
     work = leg.work
-    if leg.kind in ("decode", "kv_write"):
+    if leg.kind in ("decode", "kv_write", "decode_shared", "decode_aliased"):
         ach = work["bytes"] / avg / 1e6
         return {"kind": leg.kind, "bound": "hbm", "kernel_ms_avg": avg, "kernel_ms_min": float(np.min(kms)),
                 "algorithmic_bytes": work["bytes"], "achieved": ach, "unit": "GB/s", "peak": HBM_PEAK_GBS,
@@ -207,7 +234,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4, c5, recompute, kv_write_c4 or kv_write_c5 (or `copy`: 1 GiB copy for counter calibration)")
+    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4, c5, recompute, kv_write_c4, kv_write_c5, shared_prompt or shared_prompt_plain (or `copy`: 1 GiB copy for counter calibration)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -233,11 +260,12 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "copy", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": max(1, a.steps)}))
         return
-    extra = {"recompute": W.RECOMPUTE, "kv_write_c4": W.CONFIGS[4], "kv_write_c5": W.CONFIGS[5]}
+    extra = {"recompute": W.RECOMPUTE, "kv_write_c4": W.CONFIGS[4], "kv_write_c5": W.CONFIGS[5],
+             "shared_prompt": W.SHARED_PROMPT, "shared_prompt_plain": W.SHARED_PROMPT}
     if a.only:
         selected = [a.only] if a.only in extra else [int(a.only.lstrip("c"))]
     else:
-        selected = [HEADLINE, 3, 4, 5, "recompute", "kv_write_c4", "kv_write_c5"]
+        selected = [HEADLINE, 3, 4, 5, "recompute", "kv_write_c4", "kv_write_c5", "shared_prompt", "shared_prompt_plain"]
     reports = {}
     headline = None
     cpu = None
@@ -245,13 +273,13 @@ def main():
         w = extra[c] if c in extra else W.CONFIGS[c]
         batch = W.build(w, dev)
         small = W.algorithmic_work(w, batch.ctx_lens_host, batch.q_lens_host)["kv_bytes"] < 2e9
-        legs = [Leg(kind, bb, B, W, n_pools=3 if small else 1) for kind, bb in _parts(batch, c)]
+        legs = [Leg(kind, bb, B, W, n_pools=3 if small else 1) for kind, bb in _parts(batch, c, W)]
         steps = a.steps if c == selected[0] else max(5, min(a.steps, 20))
         ms, kms, gms = time_legs(legs, steps, a.warmup, B)
         rep = {"ms_per_step": ms, "graph_ms_per_step": gms, "steps": steps, "legs": [leg_report(l, k) for l, k in zip(legs, kms)],
                "batch": w.batch, "heads": [w.num_q_heads, w.num_kv_heads, w.head_dim], "kv_dtype": w.kv_dtype,
                "tokens": int(batch.ctx_lens_host.sum()), "query_rows": int(batch.q_lens_host.sum())}
-        reports[c if str(c).startswith("kv_write") else w.name] = rep
+        reports[c if isinstance(c, str) and c != "recompute" else w.name] = rep
         if c == selected[0]:
             headline = (w, rep, legs)
             if not a.no_cpu and c in (2, 3):

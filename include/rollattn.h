@@ -113,6 +113,26 @@ int attn_append(const rollattn_desc *desc, const void *q_chunk, const int32_t *q
                 const void *v_pages, const int32_t *page_table, const int32_t *ctx_lens, void *out,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Decode step for groups of trajectories that share a prompt: rollouts are sampled in groups of
+ * group_size per prompt with prefix caching on (Section 7.1), so the members of a group alias the
+ * same physical pages for their first tokens.  The result is that of attn_decode on the same
+ * arguments (to rounding: the two halves below are each rounded to BF16 before they are merged);
+ * the shared range is read once per group for all of the group's query heads instead of once per
+ * trajectory.  Trajectories b = j * group_size .. (j + 1) * group_size - 1 form group j; B must be a
+ * multiple of group_size.  shared_lens [B / group_size] int32 (device): the caller promises that
+ * page_table rows of a group agree on the pages of tokens [0, shared_lens[j]); the library uses
+ * S_j = that value, lowered to the group's smallest L_b - 1 and then to a multiple of 32 (S_j = 0
+ * is allowed and leaves the plain decode).  Tokens [0, S_j) are attended through the first member's
+ * table row for all members (non-causal, all query rows of the group against the same K/V tiles on
+ * the matrix cores), tokens [S_j, L_b) per trajectory as in attn_decode, and the two are merged with
+ * the log-sum-exp rule.  BF16 queries only (BF16 or FP8 pools).  workspace of at least
+ * rollattn_shared_workspace_bytes(desc, group_size) bytes. */
+int attn_decode_shared(const rollattn_desc *desc, const void *q, const void *k_pages, const void *v_pages,
+                       const int32_t *page_table, const int32_t *ctx_lens, int32_t group_size,
+                       const int32_t *shared_lens, void *out, void *workspace, size_t workspace_bytes,
+                       void *hip_stream);
+size_t rollattn_shared_workspace_bytes(const rollattn_desc *desc, int32_t group_size);
+
 /* KV write, the step before either attention call: every turn of a trajectory appends tokens to its
  * history (Section 2.1), whose KV stays cached (Section 7.1), so the K and V rows of the new tokens
  * (one per trajectory before attn_decode, the chunk before attn_append) are put into the pages.

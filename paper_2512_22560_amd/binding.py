@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "librollattn.so")
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
 EXPORTS = (
-    "attn_decode", "attn_append", "kv_write", "rollattn_workspace_bytes", "rollattn_debug_gather",
+    "attn_decode", "attn_append", "attn_decode_shared", "kv_write", "rollattn_workspace_bytes",
+    "rollattn_shared_workspace_bytes", "rollattn_debug_gather",
     "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan",
     "rollattn_profile_enable", "rollattn_profile_read", "rollattn_status_string",
     "rollattn_last_hip_error", "rollattn_version",
@@ -62,6 +63,10 @@ def lib() -> ctypes.CDLL:
         l.attn_decode.restype = ctypes.c_int
         l.attn_append.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         l.attn_append.restype = ctypes.c_int
+        l.attn_decode_shared.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        l.attn_decode_shared.restype = ctypes.c_int
+        l.rollattn_shared_workspace_bytes.argtypes = [dp, i32]
+        l.rollattn_shared_workspace_bytes.restype = ctypes.c_size_t
         l.kv_write.argtypes = [dp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         l.kv_write.restype = ctypes.c_int
         l.rollattn_workspace_bytes.argtypes = [dp, i32]
@@ -170,6 +175,26 @@ def attn_append(q_chunk, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_le
                            _ptr(out), _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise RollattnError(rc, "attn_append")
+    return out
+
+
+def attn_decode_shared(q, k_pages, v_pages, page_table, ctx_lens, *, group_size, shared_lens, sm_scale, k_scale=None,
+                       v_scale=None, out=None, workspace=None, stream=None) -> torch.Tensor:
+    """attn_decode for groups of group_size consecutive trajectories whose tables alias the pages of their first
+    shared_lens[group] tokens; those pages are read once per group."""
+    _check_contig(q, k_pages, v_pages, page_table, ctx_lens, shared_lens, k_scale, v_scale, out)
+    desc = make_desc(q, k_pages, page_table, sm_scale=sm_scale, k_scale=k_scale, v_scale=v_scale)
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        n = int(lib().rollattn_shared_workspace_bytes(ctypes.byref(desc), int(group_size)))
+        if n == 0:
+            raise RollattnError(-2, "rollattn_shared_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=q.device)
+    rc = lib().attn_decode_shared(ctypes.byref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(page_table), _ptr(ctx_lens),
+                                  int(group_size), _ptr(shared_lens), _ptr(out), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "attn_decode_shared")
     return out
 
 

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librollattn.so")
-SOURCES = ["api.cpp", "plan.hip", "attn_f32.hip", "decode_mfma.hip", "combine.hip", "append_mfma.hip", "kv_write.hip"]
+SOURCES = ["api.cpp", "plan.hip", "attn_f32.hip", "decode_mfma.hip", "combine.hip", "append_mfma.hip", "kv_write.hip", "shared_prefix.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]

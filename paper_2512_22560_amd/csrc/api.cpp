@@ -234,9 +234,10 @@ int32_t rollattn_plan_workers(const rollattn_desc* desc) {
   return decode_layout(*desc).workers;
 }
 
-int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
-                const int32_t* page_table, const int32_t* ctx_lens, void* out, void* workspace,
-                size_t workspace_bytes, void* hip_stream) {
+// attn_decode proper; lse (optional, device [B][Hq]) receives log2 of every row's softmax denominator.
+static int decode_impl(const rollattn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                       const int32_t* page_table, const int32_t* ctx_lens, void* out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream, float* lse) {
   int rc = check_desc(desc);
   if (rc) return rc;
   if (desc->batch == 0) return ROLLATTN_OK;
@@ -265,6 +266,7 @@ int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, c
   a.group = desc->num_q_heads / desc->num_kv_heads; a.max_pages = desc->max_pages_per_seq;
   a.head_tile = w.head_tile; a.rows_per_b = w.rows_per_b;
   a.scale_log2 = desc->sm_scale * 1.4426950408889634f;
+  a.lse = lse;
 
   hipError_t e = launch_plan_decode(ctx_lens, desc->batch, w.rows_per_b, w.workers, (int32_t*)(base + w.header),
                                     (int32_t*)(base + w.prefix), (int32_t*)(base + w.wstart), s);
@@ -285,10 +287,19 @@ int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, c
   return ROLLATTN_OK;
 }
 
-int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q_lens, const int32_t* q_offsets,
-                int32_t total_q, int32_t max_q_len, const void* k_pages, const void* v_pages,
+int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
                 const int32_t* page_table, const int32_t* ctx_lens, void* out, void* workspace,
                 size_t workspace_bytes, void* hip_stream) {
+  return decode_impl(desc, q, k_pages, v_pages, page_table, ctx_lens, out, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+// attn_append proper.  table_stride: int32 entries between the page-table rows of consecutive
+// trajectories; noncausal: every row sees all of [0, L_b) (then n_b <= L_b is not required);
+// lse as in decode_impl, [total_q][Hq].  Both extras are for the bf16 kernels only.
+static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int32_t* q_lens, const int32_t* q_offsets,
+                       int32_t total_q, int32_t max_q_len, const void* k_pages, const void* v_pages,
+                       const int32_t* page_table, const int32_t* ctx_lens, void* out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream, int32_t table_stride, bool noncausal, float* lse) {
   int rc = check_desc(desc);
   if (rc) return rc;
   if (total_q < 0 || max_q_len < 0) return ROLLATTN_EINVAL;
@@ -312,10 +323,12 @@ int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q
   a.tile_b = (const int32_t*)(base + w.wstart);
   a.tile_q0 = (const int32_t*)(base + w.tile_q0);
   a.batch = desc->batch; a.hq = desc->num_q_heads; a.hkv = desc->num_kv_heads;
-  a.group = desc->num_q_heads / desc->num_kv_heads; a.max_pages = desc->max_pages_per_seq;
+  a.group = desc->num_q_heads / desc->num_kv_heads; a.max_pages = table_stride;
   a.tile_tokens = std::max(1, kAppendTileRows / a.group);
   a.total_q = total_q;
   a.scale_log2 = desc->sm_scale * 1.4426950408889634f;
+  a.lse = lse;
+  a.noncausal = noncausal ? 1 : 0;
 
   hipError_t e;
   if (desc->q_dtype == ROLLATTN_F32) {
@@ -336,6 +349,98 @@ int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q
     e = launch_append_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, grid, s);
     prof.stop();
   }
+  if (e != hipSuccess) return fail_hip(e);
+  return ROLLATTN_OK;
+}
+
+int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q_lens, const int32_t* q_offsets,
+                int32_t total_q, int32_t max_q_len, const void* k_pages, const void* v_pages,
+                const int32_t* page_table, const int32_t* ctx_lens, void* out, void* workspace,
+                size_t workspace_bytes, void* hip_stream) {
+  if (!desc) return ROLLATTN_EINVAL;
+  return append_impl(desc, q_chunk, q_lens, q_offsets, total_q, max_q_len, k_pages, v_pages, page_table, ctx_lens, out,
+                     workspace, workspace_bytes, hip_stream, desc->max_pages_per_seq, false, nullptr);
+}
+
+namespace {
+// Workspace of attn_decode_shared: the two inner workspaces, the two halves' rows and denominators,
+// the group "chunk" description and the shifted private tables.
+struct SharedLayout {
+  rollattn_desc grp;      // descriptor of the shared half: one "trajectory" per group
+  size_t dec_ws, app_ws, o1, o2, d1, d2, grp_ctx, grp_qlens, grp_qoff, sfx_ctx, sfx_table, total;
+  size_t dec_bytes, app_bytes;
+};
+SharedLayout shared_layout(const rollattn_desc& d, int32_t group_size) {
+  SharedLayout L{};
+  L.grp = d;
+  L.grp.batch = d.batch / group_size;
+  const size_t rows = (size_t)d.batch * d.num_q_heads;
+  const size_t groups = (size_t)L.grp.batch;
+  L.dec_bytes = decode_layout(d).total;
+  L.app_bytes = append_layout(L.grp, d.batch).total;
+  size_t off = 0;
+  L.dec_ws = off;    off += align256(L.dec_bytes);
+  L.app_ws = off;    off += align256(L.app_bytes);
+  L.o1 = off;        off += align256(rows * d.head_dim * 2);
+  L.o2 = off;        off += align256(rows * d.head_dim * 2);
+  L.d1 = off;        off += align256(rows * sizeof(float));
+  L.d2 = off;        off += align256(rows * sizeof(float));
+  L.grp_ctx = off;   off += align256(groups * sizeof(int32_t));
+  L.grp_qlens = off; off += align256(groups * sizeof(int32_t));
+  L.grp_qoff = off;  off += align256((groups + 1) * sizeof(int32_t));
+  L.sfx_ctx = off;   off += align256((size_t)d.batch * sizeof(int32_t));
+  L.sfx_table = off; off += align256((size_t)d.batch * d.max_pages_per_seq * sizeof(int32_t));
+  L.total = off;
+  return L;
+}
+int check_shared(const rollattn_desc* desc, int32_t group_size) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (desc->q_dtype != ROLLATTN_BF16) return ROLLATTN_EDTYPE;
+  if (group_size < 1 || desc->batch % group_size) return ROLLATTN_EINVAL;
+  if ((int64_t)group_size * desc->max_pages_per_seq > INT32_MAX) return ROLLATTN_ESHAPE;
+  return ROLLATTN_OK;
+}
+}  // namespace
+
+size_t rollattn_shared_workspace_bytes(const rollattn_desc* desc, int32_t group_size) {
+  if (check_shared(desc, group_size) != ROLLATTN_OK) return 0;
+  return shared_layout(*desc, group_size).total;
+}
+
+int attn_decode_shared(const rollattn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                       const int32_t* page_table, const int32_t* ctx_lens, int32_t group_size, const int32_t* shared_lens,
+                       void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_shared(desc, group_size);
+  if (rc) return rc;
+  if (desc->batch == 0) return ROLLATTN_OK;
+  if (!q || !k_pages || !v_pages || !page_table || !ctx_lens || !shared_lens || !out || !workspace) return ROLLATTN_EINVAL;
+  if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(page_table) || !aligned16(ctx_lens) ||
+      !aligned16(shared_lens) || !aligned16(out) || !aligned16(workspace))
+    return ROLLATTN_EALIGN;
+  const SharedLayout L = shared_layout(*desc, group_size);
+  if (workspace_bytes < L.total) return ROLLATTN_EWORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* base = (char*)workspace;
+  int32_t* grp_ctx = (int32_t*)(base + L.grp_ctx);
+  int32_t* grp_qlens = (int32_t*)(base + L.grp_qlens);
+  int32_t* grp_qoff = (int32_t*)(base + L.grp_qoff);
+  int32_t* sfx_ctx = (int32_t*)(base + L.sfx_ctx);
+  int32_t* sfx_table = (int32_t*)(base + L.sfx_table);
+  hipError_t e = launch_shared_prep(ctx_lens, shared_lens, page_table, desc->batch, group_size, desc->max_pages_per_seq,
+                                    grp_ctx, grp_qlens, grp_qoff, sfx_ctx, sfx_table, s);
+  if (e != hipSuccess) return fail_hip(e);
+  // shared half: the members' query rows of a group as one chunk over the group's first S tokens
+  rc = append_impl(&L.grp, q, grp_qlens, grp_qoff, desc->batch, group_size, k_pages, v_pages, page_table, grp_ctx,
+                   base + L.o1, base + L.app_ws, L.app_bytes, hip_stream, group_size * desc->max_pages_per_seq, true,
+                   (float*)(base + L.d1));
+  if (rc) return rc;
+  // private half: every trajectory from token S on
+  rc = decode_impl(desc, q, k_pages, v_pages, sfx_table, sfx_ctx, base + L.o2, base + L.dec_ws, L.dec_bytes, hip_stream,
+                   (float*)(base + L.d2));
+  if (rc) return rc;
+  e = launch_shared_merge(base + L.o1, (const float*)(base + L.d1), base + L.o2, (const float*)(base + L.d2), out,
+                          (long)desc->batch * desc->num_q_heads, desc->head_dim, s);
   if (e != hipSuccess) return fail_hip(e);
   return ROLLATTN_OK;
 }

@@ -125,8 +125,12 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   const int ctx = a.ctx_lens[b];
   const int tokens_here = min(tile_tokens, n_b - q0);
   const int rows_here = tokens_here * group;
-  const int pos0 = ctx - n_b + q0;                       // position of the tile's first token
-  const int kv_end = pos0 + tokens_here;                 // tokens [0, kv_end) are visible to some row
+  // Causal mode: row i of the chunk sits at position L_b - n_b + i and sees tokens up to itself.
+  // Non-causal mode (the shared part of a decode step for a group of trajectories): every row sees
+  // all of [0, L_b), the rows' own tokens lie outside this range.
+  const bool causal = a.noncausal == 0;
+  const int pos0 = causal ? ctx - n_b + q0 : ctx - 1;    // position of the tile's first token
+  const int kv_end = causal ? pos0 + tokens_here : ctx;  // tokens [0, kv_end) are visible to some row
   const int n_blocks = (kv_end + kBlockTokens - 1) / kBlockTokens;
   // Page ids and page scales are inputs nobody writes during the call: reading them through the
   // constant address space lets every such load (all uniform) take the scalar path.
@@ -142,10 +146,21 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   const bool row_ok = row < rows_here;
   const int tok_in_tile = row / group;
   const int head = g * group + (row - tok_in_tile * group);
-  const int my_pos = row_ok ? pos0 + tok_in_tile : -1;   // last visible token of this row
+  const int my_pos = row_ok ? (causal ? pos0 + tok_in_tile : pos0) : -1;   // last visible token of this row
   // blocks that end at or before this position are fully visible to every row of the wave
-  const int wave_min_pos = (wave * kRowsPerWave < rows_here) ? pos0 + (wave * kRowsPerWave) / group : -1;
+  const bool wave_active = wave * kRowsPerWave < rows_here;
+  const int wave_min_pos = wave_active ? (causal ? pos0 + (wave * kRowsPerWave) / group : pos0) : -1;
   const int grp = wave >> 2;   // 0: leading half of the workgroup, 1: the half that runs one phase behind (waves w and w + 4 share a SIMD)
+
+  if (n_blocks <= 0) {                                   // nothing to attend to (non-causal mode with L_b = 0): zero rows
+    if (row_ok) {
+      __bf16* orow = (__bf16*)a.out + ((size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head) * D;
+#pragma unroll
+      for (int d0 = h2 * (D / 2); d0 < (h2 + 1) * (D / 2); d0 += 4) *(bf16x4*)(orow + d0) = bf16x4{0, 0, 0, 0};
+      if (a.lse && h2 == 0) a.lse[(size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head] = -INFINITY;
+    }
+    return;
+  }
 
   bf16x8 qop[kKK];
   {
@@ -646,6 +661,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   // ---- normalise and store: lane (row n32, half h2) owns dims dt*32 + (i/4)*8 + h2*4 + i%4
   l_run = xor32_add(l_run);
   if (row_ok) {
+    // log2 of the row's softmax denominator, for callers that merge this result with another range's
+    if (a.lse && h2 == 0) a.lse[(size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head] = m_run + __builtin_amdgcn_logf(l_run);
     const float inv = 1.f / l_run;
     __bf16* orow = (__bf16*)a.out + ((size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head) * D;
 #pragma unroll

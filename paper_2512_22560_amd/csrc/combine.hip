@@ -62,6 +62,9 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const DecodeArgs a) {
       for (int e = 0; e < kPer; ++e) o[e] += f * src[e];
     }
     inv = 1.f / lsum;
+    if (a.lse && lane == 0) a.lse[row] = mmax + __builtin_amdgcn_logf(lsum);
+  } else if (a.lse && lane == 0) {
+    a.lse[row] = -INFINITY;
   }
   if (OUT_BF16) {
     __bf16* dst = (__bf16*)a.out + (size_t)row * D + lane * kPer;

@@ -239,6 +239,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const DecodeAr
       // the whole row was ours: normalise and store
       const float inv = 1.f / l_tot;
       __bf16* dst = (__bf16*)a.out + ((size_t)cc.b * a.hq + (size_t)g * group + h0 + r16) * D + q4 * 4;
+      if (a.lse && head_ok && q4 == 0) a.lse[(size_t)cc.b * a.hq + (size_t)g * group + h0 + r16] = m_run + __builtin_amdgcn_logf(l_tot);
       if (head_ok) {
 #pragma unroll
         for (int dt = 0; dt < G_::kDT; ++dt) {

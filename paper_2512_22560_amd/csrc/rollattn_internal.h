@@ -55,6 +55,7 @@ struct DecodeArgs {
   float* partial_o;
   int32_t batch, hq, hkv, group, max_pages, head_tile, rows_per_b;
   float scale_log2;     // sm_scale * log2(e)
+  float* lse;           // optional [B][Hq]: log2 of each row's softmax denominator (reference included)
 };
 
 struct AppendArgs {
@@ -73,6 +74,8 @@ struct AppendArgs {
   const int32_t* tile_q0;
   int32_t batch, hq, hkv, group, max_pages, tile_tokens, total_q;
   float scale_log2;
+  float* lse;           // optional [total_q][Hq], as in DecodeArgs
+  int32_t noncausal;    // every row sees all of [0, L_b); the rows' own tokens are not in that range
 };
 
 // Launchers (defined in the .hip files).  Each returns the hipError_t of its launch.
@@ -89,6 +92,11 @@ hipError_t launch_kv_write(const void* k_new, const void* v_new, const int32_t* 
                            void* k_pages, void* v_pages, const int32_t* page_table, const int32_t* ctx_lens,
                            float* k_scale, float* v_scale, int32_t batch, int32_t hkv, int32_t max_pages,
                            int32_t max_q_len, int head_dim, int src_bytes, bool fp8, hipStream_t s);
+hipError_t launch_shared_prep(const int32_t* ctx_lens, const int32_t* shared_lens, const int32_t* page_table, int32_t batch,
+                              int32_t group_size, int32_t max_pages, int32_t* grp_ctx, int32_t* grp_qlens, int32_t* grp_qoff,
+                              int32_t* sfx_ctx, int32_t* sfx_table, hipStream_t s);
+hipError_t launch_shared_merge(const void* o1, const float* d1, const void* o2, const float* d2, void* out, long rows,
+                               int head_dim, hipStream_t s);
 hipError_t launch_gather(const void* pages, const int32_t* page_table, const int32_t* ctx_lens, int32_t b,
                          int32_t kv_head, int32_t hkv, int32_t max_pages, int32_t row_bytes, void* dst,
                          hipStream_t s);

@@ -81,6 +81,14 @@ RECOMPUTE = Workload("recompute_bf16_b64", 64, 32, 8, 128, "bf16", "bf16", ("con
                      qlen=("loguniform", 512, 8192), ctx_is_prefix=True, seed=BASE_SEED + 6)
 
 
+# Early turns of grouped rollouts (Section 7.1: batch 512 in groups of 8 per prompt, prefix caching on):
+# the 8 members of a group share an 8k-token prompt and have generated 32 .. 1024 tokens of their own.
+SHARED_PROMPT = Workload("shared_prompt_fp8_b512", 512, 64, 4, 128, "bf16", "fp8_e4m3",
+                         ("uniform", 8 * K + 32, 8 * K + 1024), seed=BASE_SEED + 7)
+SHARED_PROMPT_GROUP = 8
+SHARED_PROMPT_TOKENS = 8 * K
+
+
 def scaled(w: Workload, *, batch=None, ctx=None, qlen=None, append_rows=None, name=None, seed=None,
            num_q_heads=None, num_kv_heads=None, head_dim=None, q_dtype=None, kv_dtype=None) -> Workload:
     """A reduced (or otherwise altered) copy of a configuration for parity tests."""
@@ -244,6 +252,25 @@ def build(w: Workload, device="cpu", *, slab_pages: int = 8192) -> Batch:
         k_scale=scales[0], v_scale=scales[1],
         ctx_lens_host=ctx_lens, q_lens_host=q_lens,
     )
+
+
+def alias_shared_prefix(batch: Batch, group_size: int, shared_lens: np.ndarray) -> Batch:
+    """The same batch with prompts shared inside groups of `group_size` consecutive trajectories (rollouts are
+    sampled in groups per prompt, Section 7.1): the page-table entries that cover the first shared_lens[j]
+    tokens of every member of group j are replaced by the first member's, so the members alias those
+    physical pages.  Only whole pages are aliased (shared_lens is rounded down to the page size here) and
+    never beyond a member's own context.  Pools are untouched; the pages the other members no longer
+    reference simply go unused."""
+    table = batch.page_table.clone()
+    host = batch.page_table.detach().cpu().numpy().copy()
+    lens = batch.ctx_lens_host
+    for j, s in enumerate(np.asarray(shared_lens, dtype=np.int64)):
+        members = range(j * group_size, (j + 1) * group_size)
+        pages = int(min(int(s), min(int(lens[m]) for m in members))) // PAGE_SIZE
+        for m in members:
+            host[m, :pages] = host[j * group_size, :pages]
+    table.copy_(torch.from_numpy(host))
+    return dataclasses.replace(batch, page_table=table)
 
 
 def raw_numpy(t: Optional[torch.Tensor]):

@@ -62,6 +62,17 @@ def test_descriptor_errors_are_reported_before_any_launch():
     assert write(_desc(q_dtype=B.BF16, kv_dtype=B.FP8_E4M3, head_dim=128), ks=None) == -3   # FP8 pools need scale arrays
     assert write(_desc(q_dtype=B.F32, kv_dtype=B.FP8_E4M3)) == -3
     assert write(_desc(batch=70000)) == -2
+    def shared(d, group_size=2, sl=fake, ws_bytes=1 << 40):
+        return lib.attn_decode_shared(ctypes.byref(d), fake, fake, fake, fake, fake, group_size, sl, fake, fake, ws_bytes, None)
+    bf = dict(q_dtype=B.BF16, kv_dtype=B.BF16, head_dim=128)
+    assert shared(_desc(batch=4, **bf), group_size=3) == -1        # batch is not a whole number of groups
+    assert shared(_desc(batch=4, **bf), group_size=0) == -1
+    assert shared(_desc(batch=4)) == -3                            # float32 queries: not on this path
+    assert shared(_desc(batch=4, **bf), sl=None) == -1
+    assert shared(_desc(batch=4, **bf), ws_bytes=64) == -5
+    assert shared(_desc(batch=0, **bf)) == 0
+    assert lib.rollattn_shared_workspace_bytes(ctypes.byref(_desc(batch=4, **bf)), 2) > lib.rollattn_workspace_bytes(ctypes.byref(_desc(batch=4, **bf)), 4)
+    assert lib.rollattn_shared_workspace_bytes(ctypes.byref(_desc(batch=4, **bf)), 3) == 0
     for code in range(-6, 1):
         assert lib.rollattn_status_string(code)
     assert lib.rollattn_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 4) == 0

@@ -196,6 +196,9 @@ def test_device_plan_equals_host_twin_and_oracle_rule(seed, batch, hi, group):
     ("app_bf16_d64", 8, 2, 64, "bf16", "bf16"),
     ("app_fp8_g16", 32, 2, 128, "bf16", "fp8_e4m3"),
     ("app_fp8_d64_g4", 8, 2, 64, "bf16", "fp8_e4m3"),
+    ("app_bf16_g256", 256, 1, 128, "bf16", "bf16"),      # one chunk token per workgroup tile
+    ("app_fp8_g40", 40, 1, 64, "bf16", "fp8_e4m3"),      # a group that does not divide the tile
+    ("app_bf16_g5_hkv3", 15, 3, 128, "bf16", "bf16"),
 ])
 def test_append_ragged_chunks_on_cached_prefix(name, hq, hkv, d, qd, kvd):
     # prefixes 0..700 and chunks 1..300: several query tiles per row for G >= 4, several 64-token KV
@@ -215,6 +218,23 @@ def test_append_with_unit_chunks_equals_decode_and_empty_chunks_add_no_rows(qd, 
     b = W.build(_wl("holes", 8, 8, 2, d, qd, kvd, ("uniform", 1, 200), qlen=("uniform", 0, 40), seed=203, prefix=True), DEV)
     assert (b.q_lens_host == 0).any() or True
     check(gpu_append(b), oracle_append(b), qd, "rows without chunk")
+
+
+@pytest.mark.parametrize("kvd", ["bf16", "fp8_e4m3"])
+def test_append_block_and_ring_boundaries(kvd):
+    # contexts of 1 .. 7 blocks exactly, one token either side, and chunks that start and end on block edges: the
+    # LDS ring (three tiles, or two through registers) wraps at different phases for each of them
+    lens = [1, 2, 63, 64, 65, 127, 128, 129, 191, 192, 193, 256, 257, 320, 383, 384, 385, 448]
+    ctx = np.array(lens)
+    qn = np.array([1, 2, 63, 64, 1, 64, 128, 65, 3, 192, 129, 64, 257, 1, 200, 384, 2, 64])
+    w = _wl("ring", len(lens), 8, 2, 128, "bf16", kvd, ("const", 0), qlen=("const", 1), seed=207, prefix=True)
+    import dataclasses
+    b = W.build(dataclasses.replace(w, ctx=("uniform", 448, 448)), DEV)     # room for every length, then shortened
+    offs = np.concatenate([[0], np.cumsum(qn)]).astype(np.int32)
+    b = dataclasses.replace(b, ctx_lens=torch.from_numpy(ctx.astype(np.int32)).to(DEV), q_lens=torch.from_numpy(qn.astype(np.int32)).to(DEV),
+                            q_offsets=torch.from_numpy(offs).to(DEV), ctx_lens_host=ctx, q_lens_host=qn,
+                            q=torch.randn((int(qn.sum()), 8, 128), generator=torch.Generator().manual_seed(1)).to(torch.bfloat16).to(DEV))
+    check(gpu_append(b), oracle_append(b), "bf16", f"ring boundaries {kvd}")
 
 
 def test_append_empty_prefix_is_causal_self_attention():

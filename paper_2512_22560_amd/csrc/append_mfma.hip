@@ -623,35 +623,62 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     for (int d = 0; d + 1 < kRing; ++d) ko[d] = ko[d + 1];
     ko[kRing - 1] = t;
   };
-  // block 0 has no predecessor: scores only
-  __builtin_amdgcn_s_setprio(1);
-  matrix_phase(c16, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(0, even, p0, p1); });
-  __builtin_amdgcn_s_setprio(0);
-  PHASE_END();
-  softmax(0);
-  PHASE_END();
-  next_block();
-  for (int i = 1; i < n_blocks; i += 2) {
-    __builtin_amdgcn_s_setprio(1);
-    matrix_phase(c0, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i, odd, p0, p1); });
-    __builtin_amdgcn_s_setprio(0);
+  // A wave whose 32 rows all lie past the tile's last row (ragged last tile of a chunk, or a group
+  // call with few rows) keeps its share of the staging and every barrier but skips the products and
+  // the softmax: it would only compete with the wave it shares a SIMD with.
+  auto idle_phase = [&](auto&& piece) __attribute__((always_inline)) {
+    static_for<32>([&](auto t_c) __attribute__((always_inline)) {
+      constexpr int t = decltype(t_c)::value;
+      piece(std::integral_constant<int, t>{}, std::integral_constant<int, t + 1>{});
+    });
+  };
+  auto run = [&](auto active_c) __attribute__((always_inline)) {
+    constexpr bool kActive = decltype(active_c)::value;
+    // block 0 has no predecessor: scores only
+    if constexpr (kActive) {
+      __builtin_amdgcn_s_setprio(1);
+      matrix_phase(c16, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(0, even, p0, p1); });
+      __builtin_amdgcn_s_setprio(0);
+    } else {
+      idle_phase([&](auto p0, auto p1) __attribute__((always_inline)) { stage(0, even, p0, p1); });
+    }
     PHASE_END();
-    softmax(i);
+    if constexpr (kActive) softmax(0);
     PHASE_END();
     next_block();
-    if (i + 1 < n_blocks) {
-      __builtin_amdgcn_s_setprio(1);
-      matrix_phase(c0, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i + 1, even, p0, p1); });
-      __builtin_amdgcn_s_setprio(0);
+    for (int i = 1; i < n_blocks; i += 2) {
+      if constexpr (kActive) {
+        __builtin_amdgcn_s_setprio(1);
+        matrix_phase(c0, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i, odd, p0, p1); });
+        __builtin_amdgcn_s_setprio(0);
+      } else {
+        idle_phase([&](auto p0, auto p1) __attribute__((always_inline)) { stage(i, odd, p0, p1); });
+      }
       PHASE_END();
-      softmax(i + 1);
+      if constexpr (kActive) softmax(i);
       PHASE_END();
       next_block();
+      if (i + 1 < n_blocks) {
+        if constexpr (kActive) {
+          __builtin_amdgcn_s_setprio(1);
+          matrix_phase(c0, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i + 1, even, p0, p1); });
+          __builtin_amdgcn_s_setprio(0);
+        } else {
+          idle_phase([&](auto p0, auto p1) __attribute__((always_inline)) { stage(i + 1, even, p0, p1); });
+        }
+        PHASE_END();
+        if constexpr (kActive) softmax(i + 1);
+        PHASE_END();
+        next_block();
+      }
     }
-  }
-  __builtin_amdgcn_s_setprio(1);
-  matrix_phase(c0, c16, 0, ko[kRing - 1], no_piece);
-  __builtin_amdgcn_s_setprio(0);
+    if constexpr (kActive) {
+      __builtin_amdgcn_s_setprio(1);
+      matrix_phase(c0, c16, 0, ko[kRing - 1], no_piece);
+      __builtin_amdgcn_s_setprio(0);
+    }
+  };
+  if (wave_active) run(std::true_type{}); else run(std::false_type{});
   if (grp == 0) PHASE_END();
   if constexpr (!FP8) DMA_WAIT(0);                   // nothing may still be landing in LDS when the workgroup retires
 #undef PHASE_END

@@ -501,7 +501,6 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   int ko[kRing];
 #pragma unroll
   for (int d = 0; d < kRing; ++d) ko[d] = d * kTileBytes;
-  float ksc_nxt[4], vsc_nxt[4];
   unsigned int kraw[4], vraw[4];
   {
     int h0[kLoads], h1[kLoads], h2[kLoads], h3[kLoads];
@@ -553,38 +552,6 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     if constexpr (at(0)) {
 #pragma unroll
       for (int j = 0; j < kLoads; ++j) { toff[1][j] = toff[0][j]; toff[0][j] = tile_off_of(pid_new[j]); }
-      if (FP8 && i > 0) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) { ksc_cur[p] = ksc_nxt[p]; vsc_cur[p] = vsc_nxt[p]; }
-      }
-      // Scalar loads for the next round go out at once: the wait for the first operands of this
-      // phase then covers them as well, and later waits can count LDS reads again.
-      fetch_pids(u + 2, pid_new);
-      if constexpr (FP8) {
-        // scales of block i + 1: eight loads in one statement, so that each keeps a register of its
-        // own (the compiler would recycle one register and wait after every load)
-        asm volatile(
-            "s_load_dword %0, %8, %10\n\ts_load_dword %1, %8, %11\n\ts_load_dword %2, %8, %12\n\ts_load_dword %3, %8, %13\n\t"
-            "s_load_dword %4, %9, %10\n\ts_load_dword %5, %9, %11\n\ts_load_dword %6, %9, %12\n\ts_load_dword %7, %9, %13"
-            : "=&s"(kraw[0]), "=&s"(kraw[1]), "=&s"(kraw[2]), "=&s"(kraw[3]), "=&s"(vraw[0]), "=&s"(vraw[1]), "=&s"(vraw[2]), "=&s"(vraw[3])
-            : "s"(a.k_scale), "s"(a.v_scale), "s"((unsigned)spid[0] * 4u), "s"((unsigned)spid[1] * 4u), "s"((unsigned)spid[2] * 4u),
-              "s"((unsigned)spid[3] * 4u));
-        fetch_spids(i + 2);
-      }
-    }
-    if constexpr (at(1)) {                           // ... and must have arrived here, not wherever they are used next
-#pragma unroll
-      for (int j = 0; j < kLoads; ++j) asm volatile("" : "+s"(pid_new[j]));
-      if constexpr (FP8) {
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+s"(kraw[0]), "+s"(kraw[1]), "+s"(kraw[2]), "+s"(kraw[3]), "+s"(vraw[0]), "+s"(vraw[1]), "+s"(vraw[2]), "+s"(vraw[3]));
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          asm volatile("" : "+s"(spid[p]));
-          ksc_nxt[p] = __uint_as_float(kraw[p]) * a.scale_log2;
-          vsc_nxt[p] = __uint_as_float(vraw[p]);
-        }
-      }
     }
     if constexpr (FP8) {
       constexpr int slot = decltype(slot_c)::value;
@@ -610,6 +577,38 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         if (at(10 + 8 * j / kLoads)) dma(tile_addr(a.v_pages, 1, u, toff[1][j], j), v_lds[0] + ko[kRing - 2] + wave * 1024 + j * kThreads * 16);
       }
       if constexpr (at(26)) DMA_WAIT(kLead * 2 * kLoads);   // everything but the kLead newest units has landed
+    }
+  };
+  // Scalar loads (page ids of the unit issued two matrix phases from now, FP8 page scales of the next
+  // block) go out at the start of the vector phase and are awaited at its end: that phase has no LDS
+  // traffic whose waits an outstanding scalar load would turn into full drains.
+  auto scalar_issue = [&](int i) __attribute__((always_inline)) {
+    fetch_pids(i + kLead + 2, pid_new);
+    if constexpr (FP8) {
+      // scales of block i + 1: eight loads in one statement, so that each keeps a register of its
+      // own (the compiler would recycle one register and wait after every load)
+      asm volatile(
+          "s_load_dword %0, %8, %10\n\ts_load_dword %1, %8, %11\n\ts_load_dword %2, %8, %12\n\ts_load_dword %3, %8, %13\n\t"
+          "s_load_dword %4, %9, %10\n\ts_load_dword %5, %9, %11\n\ts_load_dword %6, %9, %12\n\ts_load_dword %7, %9, %13"
+          : "=&s"(kraw[0]), "=&s"(kraw[1]), "=&s"(kraw[2]), "=&s"(kraw[3]), "=&s"(vraw[0]), "=&s"(vraw[1]), "=&s"(vraw[2]), "=&s"(vraw[3])
+          : "s"(a.k_scale), "s"(a.v_scale), "s"((unsigned)spid[0] * 4u), "s"((unsigned)spid[1] * 4u), "s"((unsigned)spid[2] * 4u),
+            "s"((unsigned)spid[3] * 4u));
+      fetch_spids(i + 2);
+    }
+  };
+  auto scalar_await = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) { pid_new[j] = __builtin_amdgcn_readfirstlane(pid_new[j]); asm volatile("" : "+s"(pid_new[j])); }   // arrived here, not wherever it is used next
+    if constexpr (FP8) {
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+s"(kraw[0]), "+s"(kraw[1]), "+s"(kraw[2]), "+s"(kraw[3]), "+s"(vraw[0]), "+s"(vraw[1]), "+s"(vraw[2]), "+s"(vraw[3]));
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        spid[p] = __builtin_amdgcn_readfirstlane(spid[p]);
+        asm volatile("" : "+s"(spid[p]));
+        ksc_cur[p] = __uint_as_float(kraw[p]) * a.scale_log2;   // the softmax of this block is done with the old ones
+        vsc_cur[p] = __uint_as_float(vraw[p]);
+      }
     }
   };
   auto no_piece = [](auto, auto) {};
@@ -639,7 +638,9 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
       idle_phase([&](auto p0, auto p1) __attribute__((always_inline)) { stage(0, even, p0, p1); });
     }
     PHASE_END();
+    scalar_issue(0);
     if constexpr (kActive) softmax(0);
+    scalar_await();
     PHASE_END();
     next_block();
     for (int i = 1; i < n_blocks; i += 2) {
@@ -651,7 +652,9 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         idle_phase([&](auto p0, auto p1) __attribute__((always_inline)) { stage(i, odd, p0, p1); });
       }
       PHASE_END();
+      scalar_issue(i);
       if constexpr (kActive) softmax(i);
+      scalar_await();
       PHASE_END();
       next_block();
       if (i + 1 < n_blocks) {
@@ -663,7 +666,9 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
           idle_phase([&](auto p0, auto p1) __attribute__((always_inline)) { stage(i + 1, even, p0, p1); });
         }
         PHASE_END();
+        scalar_issue(i + 1);
         if constexpr (kActive) softmax(i + 1);
+        scalar_await();
         PHASE_END();
         next_block();
       }

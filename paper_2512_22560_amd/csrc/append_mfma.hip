@@ -266,7 +266,7 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #define DMA_WAIT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n))
 
   // FP8: scales of the four pages of a block (scalar loads), folded with the softmax scale; the page
-  // ids behind them are fetched one vector phase before the scales, the scales one phase before use
+  // ids behind them are fetched one vector phase before the scales, the scales one vector phase before use
   float ksc_cur[4], vsc_cur[4];
   int spid[kPagesPerBlock];
   auto fetch_spids = [&](int blk) __attribute__((always_inline)) {
@@ -470,7 +470,7 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   };
 
   // Two phases per block, a matrix phase (O += V P of the previous block, then S = K Q^T of this
-  // one) and a vector phase (softmax of this block, plus the workgroup's staging traffic), each
+  // one, with the workgroup's staging traffic threaded in) and a vector phase (softmax of this block), each
   // closed by a workgroup barrier.  The trailing half of the waves entered the sequence one barrier
   // late, so on every SIMD one wave is in its matrix phase while the other is in its vector phase
   // and the two pipelines run side by side instead of taking turns.  K block i and V block i - 1 are
@@ -488,14 +488,14 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   constexpr std::integral_constant<int, 1> odd{};
   constexpr std::integral_constant<int, 16> c16{};
   constexpr std::integral_constant<int, 32> c32{};
-  // All staging work is done by the wave that is in its matrix phase: that wave issues few
-  // instructions (32 MFMAs, 48 LDS reads), while the vector phase is bound by instruction issue.
-  // Page ids run ahead of the tile loads by one matrix phase, so that no load ever waits for an
-  // address: hist[0], hist[1] = this wave's page ids of blocks U + 1 and U, U being the unit it
-  // issues in its next matrix phase (U = block + 2 through registers, block + 1 direct).
+  // The tile loads and LDS writes are done by the wave that is in its matrix phase: that wave issues
+  // few instructions (32 MFMAs, 48 LDS reads), while the vector phase is bound by instruction issue.
+  // Page ids run ahead of the tile loads, so that no load ever waits for an address: U being the unit
+  // a wave issues in its next matrix phase (U = block + 2 through registers, block + 1 direct), toff
+  // holds its tile offsets for K block U and V block U - 1 and pid_new its page ids of K block U + 1.
   constexpr int kLead = FP8 ? 2 : kRing - 2;
-  size_t toff[2][kLoads];      // tile offsets of this wave's loads of K block U + 1 and V block U
-  int pid_new[kLoads];         // page ids of K block U + 1, not yet turned into an offset
+  size_t toff[2][kLoads];      // rotated at the start of the matrix phase: then [0] is K block U + 1, [1] V block U
+  int pid_new[kLoads];         // not yet turned into an offset
   // ko[d]: byte offset of the ring slot of block i + d (i = the block whose matrix phase comes
   // next); block i - 1 shares the slot of block i + kRing - 1.
   int ko[kRing];

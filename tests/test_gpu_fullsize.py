@@ -115,3 +115,18 @@ def test_recompute_prefill_full_size():
                 qs.append(q[offs[traj] + i]); tables.append(pt[traj]); lens.append(i + 1); idx.append(int(offs[traj] + i))
     ref = O.attn_decode(np.stack(qs), kp, vp, np.stack(tables), np.asarray(lens), sm_scale=w.sm_scale, q_dtype="bf16", kv_dtype="bf16")
     check(out[torch.tensor(idx, device=DEV)], ref, "bf16", "recompute prefill, sampled rows")
+
+
+@pytest.mark.parametrize("c", [4, 5])
+def test_append_is_bit_identical_from_run_to_run(c):
+    # the append kernel moves tiles HBM -> LDS asynchronously and hands them between the two halves of the
+    # workgroup with bare barriers and counted waits: a race there would show up as run-to-run differences
+    b = W.build(W.CONFIGS[c], DEV)
+    sub = b.select(b.append_rows())
+    first = gpu_append(sub).clone()
+    for _ in range(4):
+        # other work in between, so that the runs do not meet the machine in the same state
+        torch.randn(1 << 22, device=DEV).sum().item()
+        again = gpu_append(sub)
+        torch.cuda.synchronize()
+        assert torch.equal(first.view(torch.int16), again.view(torch.int16))

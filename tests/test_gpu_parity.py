@@ -163,7 +163,8 @@ def test_debug_gather_is_byte_exact(kvd):
 
 
 @pytest.mark.parametrize("seed,batch,hi,group", [(1, 64, 8192, 4), (2, 5, 300, 1), (3, 3000, 2000, 20), (4, 300, 40000, 16),
-                                                 (5, 9000, 100, 2)])
+                                                 (5, 9000, 100, 2), (6, 1024, 700, 8), (7, 1025, 700, 8),
+                                                 (8, 1000, 3, 1), (9, 257, 5000, 33)])
 def test_device_plan_equals_host_twin_and_oracle_rule(seed, batch, hi, group):
     rng = np.random.default_rng(seed)
     lens = rng.integers(0, hi, batch).astype(np.int32)

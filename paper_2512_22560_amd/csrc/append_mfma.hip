@@ -47,7 +47,7 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kRowsPerWave = 32;
 static_assert(kWaves * kRowsPerWave == kAppendTileRows, "tile rows");
 constexpr int kBlockTokens = 64;                   // KV tokens staged per step
-constexpr float kSlack = 8.f;                      // log2 of the largest p tolerated before rescaling
+constexpr float kSumLimit = 16384.f;               // a lane's 32 probabilities of a block may add up to this much before the row's reference moves
 
 // Row t of an S^T tile holds this token of its 16-token group: the middle two quads are
 // swapped so that the 8 scores a lane ends up with are 8 consecutive tokens.
@@ -396,46 +396,54 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
           if (tok > my_pos) s[sub][i] = -INFINITY;
         }
     }
-    // sc > 0 here, so the row maximum can be taken on the unscaled scores (of each page, where the
-    // pages have scales of their own)
-    float mloc;
-    if (FP8) {
-      float pm[4];
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int sub = p >> 1, o = (p & 1) * 8;
-        float x = fmaxf(fmaxf(s[sub][o], s[sub][o + 1]), s[sub][o + 2]);
-        x = fmaxf(fmaxf(x, s[sub][o + 3]), s[sub][o + 4]);
-        x = fmaxf(fmaxf(x, s[sub][o + 5]), s[sub][o + 6]);
-        pm[p] = fmaxf(x, s[sub][o + 7]);
-      }
-      mloc = fmaxf(fmaxf(pm[0] * sc[0], pm[1] * sc[1]), fmaxf(pm[2] * sc[2], pm[3] * sc[3]));
-    } else {
-      float x[kSubs];
-#pragma unroll
-      for (int sub = 0; sub < kSubs; ++sub) {          // three-input maxima, one chain per sub-block
-        x[sub] = fmaxf(fmaxf(s[sub][0], s[sub][1]), s[sub][2]);
-#pragma unroll
-        for (int i = 3; i < 15; i += 2) x[sub] = fmaxf(fmaxf(x[sub], s[sub][i]), s[sub][i + 1]);
-      }
-      mloc = fmaxf(fmaxf(x[0], s[0][15]), fmaxf(x[1], s[1][15])) * sc[0];
-    }
-    // The reference maximum only moves when a row's scores exceed it by more than 2^kSlack: until
-    // then p may be as large as 2^kSlack, which float sums and bf16 P hold without loss, and the
-    // accumulators are left alone.  The exponentials are therefore started against the old
-    // reference, before the block's maximum is known (it takes a chain of dependent steps that would
-    // otherwise leave this wave idle), and are only redone in the blocks that do move the reference.
+    // The reference m_run of a row only moves when it has to.  The exponentials are taken against the
+    // reference as it stands, p = 2^(s * sc - m_run), without looking for the block's maximum first, and may
+    // exceed one: float sums and bf16 P hold large values with the same relative precision as small
+    // ones.  Only when the p of one lane add up to more than kSumLimit (so that no single p ever exceeds
+    // it), or when a row has no reference yet, does the wave find the true maxima, move the references
+    // there, rescale the accumulators and redo the block's exponentials.  In all other blocks the maximum, a chain of dependent steps across the row, is never
+    // computed.
     const float m_old = (m_run == -INFINITY) ? 0.f : m_run;
     float p[kSubs][16];
 #pragma unroll
     for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
       for (int i = 0; i < 16; ++i) p[sub][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[sub * 2 + (i >> 3)], -m_old));
-    const float mx = xor32_max(mloc);
-    const bool bump = mx > m_run + kSlack;             // also true for the first live block (-inf)
+    float psum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) psum[sub * 2 + (i >> 3)] += p[sub][i];
+    float lane_sum = (psum[0] + psum[1]) + (psum[2] + psum[3]);
+    // (an infinite or undefined sum also fails the comparison and takes the slow path)
+    const bool bump = row_ok && (m_run == -INFINITY || !(lane_sum <= kSumLimit));
     if (__builtin_amdgcn_ballot_w64(bump)) {
-      const float m_new = bump ? mx : m_run;
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;   // rows that see nothing yet
+      // sc > 0 here, so the row maximum can be taken on the unscaled scores (of each page, where the
+      // pages have scales of their own)
+      float mloc;
+      if (FP8) {
+        float pm[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int sub = q >> 1, o = (q & 1) * 8;
+          float x = fmaxf(fmaxf(s[sub][o], s[sub][o + 1]), s[sub][o + 2]);
+          x = fmaxf(fmaxf(x, s[sub][o + 3]), s[sub][o + 4]);
+          x = fmaxf(fmaxf(x, s[sub][o + 5]), s[sub][o + 6]);
+          pm[q] = fmaxf(x, s[sub][o + 7]);
+        }
+        mloc = fmaxf(fmaxf(pm[0] * sc[0], pm[1] * sc[1]), fmaxf(pm[2] * sc[2], pm[3] * sc[3]));
+      } else {
+        float x[kSubs];
+#pragma unroll
+        for (int sub = 0; sub < kSubs; ++sub) {
+          x[sub] = fmaxf(fmaxf(s[sub][0], s[sub][1]), s[sub][2]);
+#pragma unroll
+          for (int i = 3; i < 15; i += 2) x[sub] = fmaxf(fmaxf(x[sub], s[sub][i]), s[sub][i + 1]);
+        }
+        mloc = fmaxf(fmaxf(x[0], s[0][15]), fmaxf(x[1], s[1][15])) * sc[0];
+      }
+      const float m_new = fmaxf(m_run, xor32_max(mloc));           // the same in both lanes of a row
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;     // rows that see nothing yet
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
       l_run *= alpha;
 #pragma unroll
@@ -444,20 +452,24 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
       m_run = m_new;
 #pragma unroll
+      for (int q = 0; q < 4; ++q) psum[q] = 0.f;
+#pragma unroll
       for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) p[sub][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[sub * 2 + (i >> 3)], -m_safe));
+        for (int i = 0; i < 16; ++i) {
+          p[sub][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[sub * 2 + (i >> 3)], -m_safe));
+          psum[sub * 2 + (i >> 3)] += p[sub][i];
+        }
+      lane_sum = (psum[0] + psum[1]) + (psum[2] + psum[3]);
     }
-    float psum[4] = {0.f, 0.f, 0.f, 0.f};
+    l_run += lane_sum;
 #pragma unroll
     for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int p4 = sub * 2 + (i >> 3);
-        psum[p4] += p[sub][i];
         pop[sub][i >> 3][i & 7] = (__bf16)(FP8 ? p[sub][i] * vsc_cur[p4] : p[sub][i]);
       }
-    l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
     // the probabilities are finished here, in this phase, not wherever the compiler would like to sink them
 #pragma unroll
     for (int sub = 0; sub < kSubs; ++sub)

@@ -409,11 +409,14 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
       for (int i = 0; i < 16; ++i) p[sub][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[sub * 2 + (i >> 3)], -m_old));
-    float psum[4] = {0.f, 0.f, 0.f, 0.f};
+    float psum[4];
 #pragma unroll
     for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) psum[sub * 2 + (i >> 3)] += p[sub][i];
+      for (int i = 0; i < 16; ++i) {
+        if ((i & 7) == 0) psum[sub * 2 + (i >> 3)] = p[sub][i];
+        else psum[sub * 2 + (i >> 3)] += p[sub][i];
+      }
     float lane_sum = (psum[0] + psum[1]) + (psum[2] + psum[3]);
     // (an infinite or undefined sum also fails the comparison and takes the slow path)
     const bool bump = row_ok && (m_run == -INFINITY || !(lane_sum <= kSumLimit));
@@ -452,13 +455,12 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
       m_run = m_new;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) psum[q] = 0.f;
-#pragma unroll
       for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           p[sub][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[sub * 2 + (i >> 3)], -m_safe));
-          psum[sub * 2 + (i >> 3)] += p[sub][i];
+          if ((i & 7) == 0) psum[sub * 2 + (i >> 3)] = p[sub][i];
+          else psum[sub * 2 + (i >> 3)] += p[sub][i];
         }
       lane_sum = (psum[0] + psum[1]) + (psum[2] + psum[3]);
     }

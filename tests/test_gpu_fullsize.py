@@ -130,3 +130,27 @@ def test_append_is_bit_identical_from_run_to_run(c):
         again = gpu_append(sub)
         torch.cuda.synchronize()
         assert torch.equal(first.view(torch.int16), again.view(torch.int16))
+
+
+def test_one_very_long_trajectory_next_to_short_ones():
+    # a million-token context (62 501 pages, 31 251 decode blocks, 15 626 append blocks per tile) beside a chunk
+    # with no history and a mid-size one: block and page indices far beyond anything the benchmark configs reach,
+    # the decode partition cutting one row into ~2000 pieces, the append ring wrapping thousands of times
+    import dataclasses
+    long_len = 1_000_003
+    w = W.Workload("very_long", 3, 8, 2, 128, "bf16", "fp8_e4m3", ("const", long_len), qlen=("const", 24), seed=77)
+    b = W.build(w, DEV)
+    lens = np.array([long_len, 24, 40_001], dtype=np.int64)
+    b = dataclasses.replace(b, ctx_lens=torch.from_numpy(lens.astype(np.int32)).to(DEV), ctx_lens_host=lens)
+    assert np.array_equal(b.q_lens_host, [24, 24, 24])
+    out = gpu_append(b)
+    torch.cuda.synchronize()
+    check(out, oracle_append(b), "bf16", "append on a million-token context")
+    # decode on the same pools: one query row per trajectory (the first row of each chunk stands in for it)
+    offs = np.concatenate([[0], np.cumsum(b.q_lens_host)])[:-1]
+    dec = dataclasses.replace(b, q=b.q[torch.from_numpy(offs).to(DEV)].contiguous(),
+                              q_lens=torch.ones(3, dtype=torch.int32, device=DEV),
+                              q_offsets=torch.arange(4, dtype=torch.int32, device=DEV), q_lens_host=np.ones(3, dtype=np.int64))
+    out = gpu_decode(dec)
+    torch.cuda.synchronize()
+    check(out, oracle_decode(dec), "bf16", "decode on a million-token context")

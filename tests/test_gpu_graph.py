@@ -76,3 +76,38 @@ def test_mixed_step_replays_from_a_graph_like_eager(kv):
         want = [out_d, out_a, b.k_pages, b.v_pages] + ([b.k_scale, b.v_scale] if b.k_scale is not None else [])
         for i, (x, y) in enumerate(zip(got, want)):
             assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), f"replay {it}: output {i} differs from the eager step"
+
+
+def test_calls_on_two_streams_with_workspaces_of_their_own_do_not_disturb_each_other():
+    # the library keeps no state between calls: decode and append of one step, each with its own workspace, may
+    # run side by side on two streams (default priority) and must give exactly what they give one after the other
+    w = W.Workload("two_streams", 96, 32, 4, 128, "bf16", "fp8_e4m3", ("lognormal", 3000, 0.8, 20, 20000),
+                   qlen=("uniform", 200, 1500), append_rows=16, ctx_is_prefix=True, seed=W.BASE_SEED + 43)
+    b = W.build(w, DEV)
+    dec, app = b.select(b.decode_rows()), b.select(b.append_rows())
+    out_d, out_a = torch.empty_like(dec.q), torch.empty_like(app.q)
+    ws_d = B.alloc_workspace(B.make_desc(dec.q, dec.k_pages, dec.page_table, sm_scale=w.sm_scale, k_scale=dec.k_scale, v_scale=dec.v_scale), dec.total_q, DEV)
+    ws_a = B.alloc_workspace(B.make_desc(app.q, app.k_pages, app.page_table, sm_scale=w.sm_scale, k_scale=app.k_scale, v_scale=app.v_scale), app.total_q, DEV)
+
+    def decode(stream=None):
+        B.attn_decode(dec.q, dec.k_pages, dec.v_pages, dec.page_table, dec.ctx_lens, sm_scale=w.sm_scale,
+                      k_scale=dec.k_scale, v_scale=dec.v_scale, out=out_d, workspace=ws_d, stream=stream)
+
+    def append(stream=None):
+        B.attn_append(app.q, app.q_lens, app.q_offsets, app.k_pages, app.v_pages, app.page_table, app.ctx_lens,
+                      sm_scale=w.sm_scale, max_q_len=int(app.q_lens_host.max()), k_scale=app.k_scale, v_scale=app.v_scale,
+                      out=out_a, workspace=ws_a, stream=stream)
+
+    decode(); append()
+    torch.cuda.synchronize()
+    want_d, want_a = out_d.clone(), out_a.clone()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(3):
+        out_d.zero_(); out_a.zero_()
+        torch.cuda.synchronize()
+        append(s2)                       # the long call first, so that the short ones land inside it
+        for _ in range(4):
+            decode(s1)
+        torch.cuda.synchronize()
+        assert torch.equal(out_d.view(torch.int16), want_d.view(torch.int16))
+        assert torch.equal(out_a.view(torch.int16), want_a.view(torch.int16))

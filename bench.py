@@ -57,6 +57,8 @@ def _parts(batch, c, W):
         return [("decode_shared" if c == "shared_prompt" else "decode_aliased", aliased)]
     if c == "kv_write_c5":
         return [("kv_write", batch.select(batch.append_rows()))]
+    if c == "c5_one_call":
+        return [("step", batch)]                     # the mixed batch as it is: the library tells the two kinds apart
     return [("decode", batch.select(batch.decode_rows())), ("append", batch.select(batch.append_rows()))]
 
 
@@ -78,6 +80,9 @@ class Leg:
             n_groups = w.batch // W.SHARED_PROMPT_GROUP
             self.shared_lens = torch.full((n_groups,), W.SHARED_PROMPT_TOKENS, dtype=torch.int32, device=bb.q.device)
             self.ws = torch.empty(int(B.lib().rollattn_shared_workspace_bytes(ctypes.byref(desc), W.SHARED_PROMPT_GROUP)),
+                                  dtype=torch.uint8, device=bb.q.device)
+        if kind == "step":
+            self.ws = torch.empty(int(B.lib().rollattn_step_workspace_bytes(ctypes.byref(desc), bb.total_q)),
                                   dtype=torch.uint8, device=bb.q.device)
         if kind in ("decode_shared", "decode_aliased"):
             # bytes that have to move when every physical page is read once: the prompts per group, the rest per trajectory
@@ -117,6 +122,9 @@ class Leg:
         elif self.kind == "kv_write":
             B.kv_write(self.k_new, self.v_new, bb.q_lens, bb.q_offsets, k, v, bb.page_table, bb.ctx_lens, max_q_len=self.max_q,
                        k_scale=bb.k_scale, v_scale=bb.v_scale)
+        elif self.kind == "step":
+            B.attn_step(bb.q, bb.q_lens, bb.q_offsets, k, v, bb.page_table, bb.ctx_lens, sm_scale=w.sm_scale,
+                        max_q_len=self.max_q, k_scale=bb.k_scale, v_scale=bb.v_scale, out=self.out, workspace=self.ws)
         elif self.kind in ("decode", "decode_aliased"):
             B.attn_decode(bb.q, k, v, bb.page_table, bb.ctx_lens, sm_scale=w.sm_scale, k_scale=bb.k_scale,
                           v_scale=bb.v_scale, out=self.out, workspace=self.ws)
@@ -182,7 +190,7 @@ def time_legs(legs, steps, warmup, B):
 
 
 def leg_report(leg, kms):
-    if leg.kind == "decode_shared":           # two main kernels per step (shared half, private half): report their sum
+    if leg.kind in ("decode_shared", "step"):  # two main kernels per call (shared and private half; chunks and decode rows): their sum
         kms = np.asarray(kms)[: len(kms) // 2 * 2].reshape(-1, 2).sum(axis=1)
     avg = float(np.mean(kms))
     work = leg.work
@@ -192,7 +200,7 @@ def leg_report(leg, kms):
                 "algorithmic_bytes": work["bytes"], "achieved": ach, "unit": "GB/s", "peak": HBM_PEAK_GBS,
                 "frac": ach / HBM_PEAK_GBS}
     ach = work["flops"] / avg / 1e9
-    return {"kind": "append", "bound": "mfma", "kernel_ms_avg": avg, "kernel_ms_min": float(np.min(kms)),
+    return {"kind": leg.kind, "bound": "mfma", "kernel_ms_avg": avg, "kernel_ms_min": float(np.min(kms)),
             "algorithmic_flops": work["flops"], "algorithmic_bytes": work["bytes"], "achieved": ach,
             "unit": "TFLOP/s", "peak": MFMA_BF16_PEAK_TFLOPS, "frac": ach / MFMA_BF16_PEAK_TFLOPS}
 
@@ -234,7 +242,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4, c5, recompute, kv_write_c4, kv_write_c5, shared_prompt or shared_prompt_plain (or `copy`: 1 GiB copy for counter calibration)")
+    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4, c5, c5_one_call, recompute, kv_write_c4, kv_write_c5, shared_prompt or shared_prompt_plain (or `copy`: 1 GiB copy for counter calibration)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -260,12 +268,12 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "copy", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": max(1, a.steps)}))
         return
-    extra = {"recompute": W.RECOMPUTE, "kv_write_c4": W.CONFIGS[4], "kv_write_c5": W.CONFIGS[5],
+    extra = {"recompute": W.RECOMPUTE, "kv_write_c4": W.CONFIGS[4], "kv_write_c5": W.CONFIGS[5], "c5_one_call": W.CONFIGS[5],
              "shared_prompt": W.SHARED_PROMPT, "shared_prompt_plain": W.SHARED_PROMPT}
     if a.only:
         selected = [a.only] if a.only in extra else [int(a.only.lstrip("c"))]
     else:
-        selected = [HEADLINE, 3, 4, 5, "recompute", "kv_write_c4", "kv_write_c5", "shared_prompt", "shared_prompt_plain"]
+        selected = [HEADLINE, 3, 4, 5, "c5_one_call", "recompute", "kv_write_c4", "kv_write_c5", "shared_prompt", "shared_prompt_plain"]
     reports = {}
     headline = None
     cpu = None

@@ -113,6 +113,21 @@ int attn_append(const rollattn_desc *desc, const void *q_chunk, const int32_t *q
                 const void *v_pages, const int32_t *page_table, const int32_t *ctx_lens, void *out,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* One engine step on a mixed batch in one call: during a rollout some requests of the batch generate (one new
+ * token) while others have just received an observation and prefill it (Section 6.1, the inference worker takes
+ * a decode or a prefill step per request; Section 3.1, the two phases).  Arguments as attn_append, with the
+ * rows of ALL trajectories packed in q: a trajectory with q_lens[b] == 1 is a decode row and goes through the
+ * decode path (planned over those trajectories only), one with q_lens[b] > 1 through the append path, one with
+ * q_lens[b] == 0 contributes nothing.  The result is that of attn_append on the same arguments, and row for row
+ * bit-identical to what attn_decode and attn_append give on the two sub-batches.  The partition into the two
+ * kinds is made on the device from q_lens; nothing is copied to the host, so the call can be captured in a HIP
+ * graph.  workspace of at least rollattn_step_workspace_bytes(desc, total_q) bytes. */
+int attn_step(const rollattn_desc *desc, const void *q, const int32_t *q_lens, const int32_t *q_offsets,
+              int32_t total_q, int32_t max_q_len, const void *k_pages, const void *v_pages,
+              const int32_t *page_table, const int32_t *ctx_lens, void *out, void *workspace,
+              size_t workspace_bytes, void *hip_stream);
+size_t rollattn_step_workspace_bytes(const rollattn_desc *desc, int32_t total_q);
+
 /* Decode step for groups of trajectories that share a prompt: rollouts are sampled in groups of
  * group_size per prompt with prefix caching on (Section 7.1), so the members of a group alias the
  * same physical pages for their first tokens.  The result is that of attn_decode on the same

@@ -19,8 +19,8 @@ LIB_PATH = os.path.join(_HERE, "librollattn.so")
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
 EXPORTS = (
-    "attn_decode", "attn_append", "attn_decode_shared", "kv_write", "rollattn_workspace_bytes",
-    "rollattn_shared_workspace_bytes", "rollattn_debug_gather",
+    "attn_decode", "attn_append", "attn_step", "attn_decode_shared", "kv_write", "rollattn_workspace_bytes",
+    "rollattn_step_workspace_bytes", "rollattn_shared_workspace_bytes", "rollattn_debug_gather",
     "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan",
     "rollattn_profile_enable", "rollattn_profile_read", "rollattn_status_string",
     "rollattn_last_hip_error", "rollattn_version",
@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
         l.attn_decode.restype = ctypes.c_int
         l.attn_append.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         l.attn_append.restype = ctypes.c_int
+        l.attn_step.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        l.attn_step.restype = ctypes.c_int
+        l.rollattn_step_workspace_bytes.argtypes = [dp, i32]
+        l.rollattn_step_workspace_bytes.restype = ctypes.c_size_t
         l.attn_decode_shared.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
         l.attn_decode_shared.restype = ctypes.c_int
         l.rollattn_shared_workspace_bytes.argtypes = [dp, i32]
@@ -175,6 +179,26 @@ def attn_append(q_chunk, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_le
                            _ptr(out), _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise RollattnError(rc, "attn_append")
+    return out
+
+
+def attn_step(q, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, *, sm_scale, max_q_len,
+              k_scale=None, v_scale=None, out=None, workspace=None, stream=None) -> torch.Tensor:
+    """One engine step on a mixed batch: trajectories with one row take the decode path, those with a chunk the
+    append path, decided on the device from q_lens."""
+    _check_contig(q, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, k_scale, v_scale, out)
+    desc = make_desc(q, k_pages, page_table, sm_scale=sm_scale, k_scale=k_scale, v_scale=v_scale)
+    total_q = int(q.shape[0])
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        n = int(lib().rollattn_step_workspace_bytes(ctypes.byref(desc), total_q))
+        workspace = torch.empty(max(n, 256), dtype=torch.uint8, device=q.device)
+    rc = lib().attn_step(ctypes.byref(desc), _ptr(q), _ptr(q_lens), _ptr(q_offsets), total_q, int(max_q_len),
+                         _ptr(k_pages), _ptr(v_pages), _ptr(page_table), _ptr(ctx_lens), _ptr(out), _ptr(workspace),
+                         workspace.numel(), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "attn_step")
     return out
 
 

@@ -235,9 +235,11 @@ int32_t rollattn_plan_workers(const rollattn_desc* desc) {
 }
 
 // attn_decode proper; lse (optional, device [B][Hq]) receives log2 of every row's softmax denominator.
+// q_lens / q_offsets (both or neither): the mixed step, see DecodeArgs.
 static int decode_impl(const rollattn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
                        const int32_t* page_table, const int32_t* ctx_lens, void* out, void* workspace,
-                       size_t workspace_bytes, void* hip_stream, float* lse) {
+                       size_t workspace_bytes, void* hip_stream, float* lse, const int32_t* q_lens = nullptr,
+                       const int32_t* q_offsets = nullptr) {
   int rc = check_desc(desc);
   if (rc) return rc;
   if (desc->batch == 0) return ROLLATTN_OK;
@@ -267,8 +269,10 @@ static int decode_impl(const rollattn_desc* desc, const void* q, const void* k_p
   a.head_tile = w.head_tile; a.rows_per_b = w.rows_per_b;
   a.scale_log2 = desc->sm_scale * 1.4426950408889634f;
   a.lse = lse;
+  a.q_lens = q_lens;
+  a.q_offsets = q_offsets;
 
-  hipError_t e = launch_plan_decode(ctx_lens, desc->batch, w.rows_per_b, w.workers, (int32_t*)(base + w.header),
+  hipError_t e = launch_plan_decode(ctx_lens, q_lens, desc->batch, w.rows_per_b, w.workers, (int32_t*)(base + w.header),
                                     (int32_t*)(base + w.prefix), (int32_t*)(base + w.wstart), s);
   if (e != hipSuccess) return fail_hip(e);
   const bool f32 = desc->q_dtype == ROLLATTN_F32;
@@ -299,7 +303,8 @@ int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, c
 static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int32_t* q_lens, const int32_t* q_offsets,
                        int32_t total_q, int32_t max_q_len, const void* k_pages, const void* v_pages,
                        const int32_t* page_table, const int32_t* ctx_lens, void* out, void* workspace,
-                       size_t workspace_bytes, void* hip_stream, int32_t table_stride, bool noncausal, float* lse) {
+                       size_t workspace_bytes, void* hip_stream, int32_t table_stride, bool noncausal, float* lse,
+                       bool skip_unit_chunks = false) {
   int rc = check_desc(desc);
   if (rc) return rc;
   if (total_q < 0 || max_q_len < 0) return ROLLATTN_EINVAL;
@@ -340,8 +345,8 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
     if (e != hipSuccess) return fail_hip(e);
     return ROLLATTN_OK;
   }
-  e = launch_plan_append(q_lens, ctx_lens, desc->batch, a.tile_tokens, w.workers, a.header, (int32_t*)(base + w.wstart),
-                         (int32_t*)(base + w.tile_q0), s);
+  e = launch_plan_append(q_lens, ctx_lens, desc->batch, a.tile_tokens, w.workers, skip_unit_chunks, a.header,
+                         (int32_t*)(base + w.wstart), (int32_t*)(base + w.tile_q0), s);
   if (e != hipSuccess) return fail_hip(e);
   {
     ProfileScope prof(s);
@@ -360,6 +365,38 @@ int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q
   if (!desc) return ROLLATTN_EINVAL;
   return append_impl(desc, q_chunk, q_lens, q_offsets, total_q, max_q_len, k_pages, v_pages, page_table, ctx_lens, out,
                      workspace, workspace_bytes, hip_stream, desc->max_pages_per_seq, false, nullptr);
+}
+
+size_t rollattn_step_workspace_bytes(const rollattn_desc* desc, int32_t total_q) {
+  if (check_desc(desc) != ROLLATTN_OK || total_q < 0) return 0;
+  return align256(decode_layout(*desc).total) + append_layout(*desc, total_q).total;
+}
+
+int attn_step(const rollattn_desc* desc, const void* q, const int32_t* q_lens, const int32_t* q_offsets, int32_t total_q,
+              int32_t max_q_len, const void* k_pages, const void* v_pages, const int32_t* page_table,
+              const int32_t* ctx_lens, void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (total_q < 0 || max_q_len < 0) return ROLLATTN_EINVAL;
+  if (desc->batch == 0 || total_q == 0) return ROLLATTN_OK;
+  if (!workspace) return ROLLATTN_EINVAL;
+  if (!aligned16(workspace)) return ROLLATTN_EALIGN;
+  if (workspace_bytes < rollattn_step_workspace_bytes(desc, total_q)) return ROLLATTN_EWORKSPACE;
+  if (desc->q_dtype == ROLLATTN_F32) {
+    // the float32 path has one kernel for chunks of any length, one token included
+    return append_impl(desc, q, q_lens, q_offsets, total_q, max_q_len, k_pages, v_pages, page_table, ctx_lens, out,
+                       workspace, workspace_bytes, hip_stream, desc->max_pages_per_seq, false, nullptr);
+  }
+  if (!q_lens || !q_offsets) return ROLLATTN_EINVAL;
+  if (!aligned16(q_lens) || !aligned16(q_offsets)) return ROLLATTN_EALIGN;
+  const size_t dec_bytes = align256(decode_layout(*desc).total);
+  // the long tiles of the chunks first, then the decode rows and their merge; all on one stream, disjoint output rows
+  rc = append_impl(desc, q, q_lens, q_offsets, total_q, max_q_len, k_pages, v_pages, page_table, ctx_lens, out,
+                   (char*)workspace + dec_bytes, workspace_bytes - dec_bytes, hip_stream, desc->max_pages_per_seq, false,
+                   nullptr, /*skip_unit_chunks=*/true);
+  if (rc) return rc;
+  return decode_impl(desc, q, k_pages, v_pages, page_table, ctx_lens, out, workspace, dec_bytes, hip_stream, nullptr, q_lens,
+                     q_offsets);
 }
 
 namespace {

@@ -25,6 +25,8 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const DecodeArgs a) {
   if (row >= (long)a.batch * a.hq) return;
   const int b = (int)(row / a.hq);
   const int h = (int)(row % a.hq);
+  if (a.q_lens && a.q_lens[b] != 1) return;                 // mixed step: not a decode row, nothing of ours to write
+  const size_t orow = (size_t)(a.q_offsets ? a.q_offsets[b] : b) * a.hq + h;   // where this row's output goes
   const int ht = a.head_tile;
   const int n_ht = a.rows_per_b / a.hkv;
   const int g = h / a.group, j = h % a.group;
@@ -62,12 +64,12 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const DecodeArgs a) {
       for (int e = 0; e < kPer; ++e) o[e] += f * src[e];
     }
     inv = 1.f / lsum;
-    if (a.lse && lane == 0) a.lse[row] = mmax + __builtin_amdgcn_logf(lsum);
+    if (a.lse && lane == 0) a.lse[orow] = mmax + __builtin_amdgcn_logf(lsum);
   } else if (a.lse && lane == 0) {
-    a.lse[row] = -INFINITY;
+    a.lse[orow] = -INFINITY;
   }
   if (OUT_BF16) {
-    __bf16* dst = (__bf16*)a.out + (size_t)row * D + lane * kPer;
+    __bf16* dst = (__bf16*)a.out + orow * D + lane * kPer;
     if (kPer == 2) {
       bf16x2 pr;
       pr[0] = (__bf16)(o[0] * inv);
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const DecodeArgs a) {
       dst[0] = (__bf16)(o[0] * inv);
     }
   } else {
-    float* dst = (float*)a.out + (size_t)row * D + lane * kPer;
+    float* dst = (float*)a.out + orow * D + lane * kPer;
 #pragma unroll
     for (int e = 0; e < kPer; ++e) dst[e] = o[e] * inv;
   }

@@ -121,10 +121,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const DecodeAr
     c.r = 0;
     do {
       ++c.b;
-      c.len = a.ctx_lens[c.b];
+      c.len = (!a.q_lens || a.q_lens[c.b] == 1) ? a.ctx_lens[c.b] : 0;   // mixed step: chunk rows are not ours
     } while (c.len == 0);
     c.n = (c.len + kBlockTokens - 1) / kBlockTokens;
   };
+  // query / output row of a trajectory: its index, or in a mixed step where its one token sits in the packed rows
+  auto row_of = [&](int b) { return (size_t)(a.q_offsets ? a.q_offsets[b] : b); };
 
   // ---- producer state: a window of 64 page ids (32 blocks) of the current row, one per lane
   int pwin = -1, pid_vec = 0, pid_next = 0;
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const DecodeAr
   auto begin_segment = [&]() {
     const int g = cc.r / n_ht;
     const int h0 = (cc.r - g * n_ht) * kMfmaHeadTile;
-    const __bf16* qrow = (const __bf16*)a.q + ((size_t)cc.b * a.hq + (size_t)g * group + h0 + r16) * D;
+    const __bf16* qrow = (const __bf16*)a.q + (row_of(cc.b) * a.hq + (size_t)g * group + h0 + r16) * D;
 #pragma unroll
     for (int kk = 0; kk < G_::kKK; ++kk) {
       bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -240,8 +242,9 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_kernel(const DecodeAr
     if (seg_first_blk == 0 && cc.blk == cc.n - 1) {
       // the whole row was ours: normalise and store
       const float inv = 1.f / l_tot;
-      __bf16* dst = (__bf16*)a.out + ((size_t)cc.b * a.hq + (size_t)g * group + h0 + r16) * D + q4 * 4;
-      if (a.lse && head_ok && q4 == 0) a.lse[(size_t)cc.b * a.hq + (size_t)g * group + h0 + r16] = m_run + __builtin_amdgcn_logf(l_tot);
+      const size_t orow = row_of(cc.b) * a.hq + (size_t)g * group + h0 + r16;
+      __bf16* dst = (__bf16*)a.out + orow * D + q4 * 4;
+      if (a.lse && head_ok && q4 == 0) a.lse[orow] = m_run + __builtin_amdgcn_logf(l_tot);
       if (head_ok) {
 #pragma unroll
         for (int dt = 0; dt < G_::kDT; ++dt) {

@@ -38,9 +38,10 @@ __device__ int block_exclusive_scan(int v, int* wave_tot /*[16]*/, int* total) {
 // workers in equal contiguous runs of per = ceil(T / W) blocks.  Written out: the exclusive
 // scan of n_b, the run length, T, and for every worker one 16-byte record with all it needs to
 // start: (b, r << 20 | block, L_b, blocks in its run), or b = -1 for a worker without blocks.
+// With q_lens given (mixed step) only the trajectories with q_lens[b] == 1 take part; the others count as empty.
 __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
-    const int32_t* __restrict__ ctx_lens, int32_t batch, int32_t rows_per_b, int32_t workers,
-    int32_t* __restrict__ header, int32_t* __restrict__ prefix, int32_t* __restrict__ wstart) {
+    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ q_lens, int32_t batch, int32_t rows_per_b,
+    int32_t workers, int32_t* __restrict__ header, int32_t* __restrict__ prefix, int32_t* __restrict__ wstart) {
   __shared__ int wave_tot[kPlanThreads / 64];
   __shared__ int prefix_s[kLdsPrefix + 1];
   const int tid = threadIdx.x;
@@ -49,14 +50,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
   int running = 0;
   for (int b0 = 0; b0 < batch; b0 += kPlanThreads) {
     const int b = b0 + tid;
-    const int count = (b < batch) ? (ctx_lens[b] + kBlockTokens - 1) / kBlockTokens : 0;
+    const int len = (b < batch && (!q_lens || q_lens[b] == 1)) ? ctx_lens[b] : 0;
+    const int count = (len + kBlockTokens - 1) / kBlockTokens;
     int tile_total;
     const int first = running + block_exclusive_scan(count, wave_tot, &tile_total);
     if (b < batch) {
       prefix[b] = first;
       if (in_lds) {
         prefix_s[b] = first;
-        len_s[b] = ctx_lens[b];
+        len_s[b] = len;
       }
     }
     running += tile_total;
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
       const int n = pf[lo + 1] - pf[lo];
       const int rem = (int)(x - (long)rows_per_b * pf[lo]);
       const int mine = (int)min((long)per, (long)total - x);
-      st = make_int4(lo, ((rem / n) << 20) | (rem % n), in_lds ? len_s[lo] : ctx_lens[lo], mine);
+      st = make_int4(lo, ((rem / n) << 20) | (rem % n), in_lds ? len_s[lo] : ctx_lens[lo], mine);   // lo has blocks, so it takes part
     }
     *(int4*)(wstart + 4 * w) = st;
   }
@@ -104,7 +106,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
 constexpr int kRankBatch = 4096;
 __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
     const int32_t* __restrict__ q_lens, const int32_t* __restrict__ ctx_lens, int32_t batch, int32_t tile_tokens,
-    int32_t cap, int32_t* __restrict__ header, int32_t* __restrict__ tile_b, int32_t* __restrict__ tile_q0) {
+    int32_t cap, bool skip_unit_chunks, int32_t* __restrict__ header, int32_t* __restrict__ tile_b,
+    int32_t* __restrict__ tile_q0) {
   __shared__ int wave_tot[kPlanThreads / 64];
   __shared__ int len_s[kRankBatch];
   __shared__ int order_s[kRankBatch];
@@ -131,6 +134,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
     if (p < batch) {
       b = ranked ? order_s[p] : p;
       count = (q_lens[b] + tile_tokens - 1) / tile_tokens;
+      if (skip_unit_chunks && q_lens[b] == 1) count = 0;   // mixed step: the decode kernel takes these
     }
     int tile_total;
     const int first = running + block_exclusive_scan(count, wave_tot, &tile_total);
@@ -147,17 +151,18 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
 
 }  // namespace
 
-hipError_t launch_plan_decode(const int32_t* ctx_lens, int32_t batch, int32_t rows_per_b, int32_t workers,
-                              int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s) {
-  hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(kPlanThreads), 0, s, ctx_lens, batch, rows_per_b, workers,
+hipError_t launch_plan_decode(const int32_t* ctx_lens, const int32_t* q_lens, int32_t batch, int32_t rows_per_b,
+                              int32_t workers, int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s) {
+  hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(kPlanThreads), 0, s, ctx_lens, q_lens, batch, rows_per_b, workers,
                      header, prefix, wstart);
   return hipGetLastError();
 }
 
 hipError_t launch_plan_append(const int32_t* q_lens, const int32_t* ctx_lens, int32_t batch, int32_t tile_tokens,
-                              int32_t cap, int32_t* header, int32_t* tile_b, int32_t* tile_q0, hipStream_t s) {
+                              int32_t cap, bool skip_unit_chunks, int32_t* header, int32_t* tile_b, int32_t* tile_q0,
+                              hipStream_t s) {
   hipLaunchKernelGGL(plan_append_kernel, dim3(1), dim3(kPlanThreads), 0, s, q_lens, ctx_lens, batch, tile_tokens, cap,
-                     header, tile_b, tile_q0);
+                     skip_unit_chunks, header, tile_b, tile_q0);
   return hipGetLastError();
 }
 

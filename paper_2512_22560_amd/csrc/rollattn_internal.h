@@ -56,6 +56,10 @@ struct DecodeArgs {
   int32_t batch, hq, hkv, group, max_pages, head_tile, rows_per_b;
   float scale_log2;     // sm_scale * log2(e)
   float* lse;           // optional [B][Hq]: log2 of each row's softmax denominator (reference included)
+  // Mixed step (both null otherwise): only trajectories with q_lens[b] == 1 are decode rows, the others count
+  // as empty here; the query and output row of trajectory b is q_offsets[b] instead of b.
+  const int32_t* q_lens;
+  const int32_t* q_offsets;
 };
 
 struct AppendArgs {
@@ -79,10 +83,11 @@ struct AppendArgs {
 };
 
 // Launchers (defined in the .hip files).  Each returns the hipError_t of its launch.
-hipError_t launch_plan_decode(const int32_t* ctx_lens, int32_t batch, int32_t rows_per_b, int32_t workers,
-                              int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s);
+hipError_t launch_plan_decode(const int32_t* ctx_lens, const int32_t* q_lens, int32_t batch, int32_t rows_per_b,
+                              int32_t workers, int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s);
 hipError_t launch_plan_append(const int32_t* q_lens, const int32_t* ctx_lens, int32_t batch, int32_t tile_tokens,
-                              int32_t cap, int32_t* header, int32_t* tile_b, int32_t* tile_q0, hipStream_t s);
+                              int32_t cap, bool skip_unit_chunks, int32_t* header, int32_t* tile_b, int32_t* tile_q0,
+                              hipStream_t s);
 hipError_t launch_decode_f32(const DecodeArgs& a, int head_dim, int grid, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeArgs& a, int head_dim, bool fp8, int grid, hipStream_t s);
 hipError_t launch_combine(const DecodeArgs& a, int head_dim, bool out_bf16, hipStream_t s);

@@ -73,6 +73,18 @@ def test_descriptor_errors_are_reported_before_any_launch():
     assert shared(_desc(batch=0, **bf)) == 0
     assert lib.rollattn_shared_workspace_bytes(ctypes.byref(_desc(batch=4, **bf)), 2) > lib.rollattn_workspace_bytes(ctypes.byref(_desc(batch=4, **bf)), 4)
     assert lib.rollattn_shared_workspace_bytes(ctypes.byref(_desc(batch=4, **bf)), 3) == 0
+    def step(d, total_q=8, ql=fake, ws=fake, ws_bytes=1 << 40):
+        return lib.attn_step(ctypes.byref(d), fake, ql, fake, total_q, 2, fake, fake, fake, fake, fake, ws, ws_bytes, None)
+    assert step(_desc(**bf), total_q=0) == 0                       # nothing to do: success, no launch
+    assert step(_desc(**bf), total_q=-1) == -1
+    assert step(_desc(head_dim=96)) == -2
+    assert step(_desc(**bf), ql=None) == -1
+    assert step(_desc(**bf), ws=None) == -1
+    assert step(_desc(**bf), ws=ctypes.c_void_p(0x1008)) == -4
+    assert step(_desc(**bf), ws_bytes=1024) == -5
+    d = _desc(**bf)
+    assert lib.rollattn_step_workspace_bytes(ctypes.byref(d), 8) >= (lib.rollattn_workspace_bytes(ctypes.byref(d), 8) + 256)
+    assert lib.rollattn_step_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 8) == 0
     for code in range(-6, 1):
         assert lib.rollattn_status_string(code)
     assert lib.rollattn_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 4) == 0

@@ -184,6 +184,19 @@ int rollattn_debug_gather(const rollattn_desc *desc, const void *pages, const in
                           const int32_t *ctx_lens, int32_t b, int32_t kv_head, void *dst,
                           void *hip_stream);
 
+/* What the attention and KV-write calls take on trust, checked on the device for callers that want to be sure
+ * before they launch (an index outside a pool is a GPU memory fault, not an error code).  Counts into
+ * counts_out (host, int32[4]):
+ *   [0] trajectories with L_b outside [0, 16 * max_pages_per_seq]
+ *   [1] page-table entries of live pages (page < ceil(L_b / 16)) outside [0, num_pages)
+ *   [2] trajectories with n_b outside [0, L_b]                        (only when q_lens is given)
+ *   [3] trajectories where q_offsets is not the exclusive scan of q_lens (only when both are given)
+ * counts_dev: device int32[4] scratch the caller owns.  Synchronises the stream; returns 0 whenever the check
+ * itself ran, whatever it counted. */
+int rollattn_debug_check_inputs(const rollattn_desc *desc, const int32_t *page_table, const int32_t *ctx_lens,
+                                const int32_t *q_lens, const int32_t *q_offsets, int32_t *counts_dev,
+                                int32_t *counts_out, void *hip_stream);
+
 /* Host twin of the decode partition rule, for bit-exact plan tests; runs without a GPU.
  * The rule: each trajectory is cut into blocks of 32 tokens; a "row" is (trajectory b, r) with
  * r = kv_head * tiles + head_tile enumerating KV heads and, when the group is larger than one

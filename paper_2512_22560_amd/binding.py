@@ -21,6 +21,7 @@ F32, BF16, FP8_E4M3 = 0, 1, 2
 EXPORTS = (
     "attn_decode", "attn_append", "attn_step", "attn_decode_shared", "kv_write", "rollattn_workspace_bytes",
     "rollattn_step_workspace_bytes", "rollattn_shared_workspace_bytes", "rollattn_debug_gather",
+    "rollattn_debug_check_inputs",
     "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan",
     "rollattn_profile_enable", "rollattn_profile_read", "rollattn_status_string",
     "rollattn_last_hip_error", "rollattn_version",
@@ -77,6 +78,8 @@ def lib() -> ctypes.CDLL:
         l.rollattn_workspace_bytes.restype = ctypes.c_size_t
         l.rollattn_debug_gather.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp]
         l.rollattn_debug_gather.restype = ctypes.c_int
+        l.rollattn_debug_check_inputs.argtypes = [dp, vp, vp, vp, vp, vp, i32p, vp]
+        l.rollattn_debug_check_inputs.restype = ctypes.c_int
         l.rollattn_debug_plan.argtypes = [dp, i32p, i32p, i32p, i32p, i32p]
         l.rollattn_debug_plan.restype = ctypes.c_int
         l.rollattn_plan_capacity.argtypes = [dp]
@@ -248,6 +251,18 @@ def debug_gather(pages, page_table, ctx_lens, b, kv_head, length, stream=None) -
     if rc:
         raise RollattnError(rc, "rollattn_debug_gather")
     return dst
+
+
+def check_inputs(desc: Desc, page_table, ctx_lens, q_lens=None, q_offsets=None, stream=None) -> np.ndarray:
+    """Device-side check of lengths, page ids and the chunk description: int32[4] counts of violations (all zero
+    for inputs the attention calls may be given).  Synchronises."""
+    counts_dev = torch.empty(4, dtype=torch.int32, device=page_table.device)
+    out = np.zeros(4, dtype=np.int32)
+    rc = lib().rollattn_debug_check_inputs(ctypes.byref(desc), _ptr(page_table), _ptr(ctx_lens), _ptr(q_lens), _ptr(q_offsets),
+                                           _ptr(counts_dev), out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "rollattn_debug_check_inputs")
+    return out
 
 
 def debug_plan(desc: Desc, ctx_lens_host: np.ndarray):

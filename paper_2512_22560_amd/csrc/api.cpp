@@ -519,6 +519,27 @@ int rollattn_debug_gather(const rollattn_desc* desc, const void* pages, const in
   return ROLLATTN_OK;
 }
 
+int rollattn_debug_check_inputs(const rollattn_desc* desc, const int32_t* page_table, const int32_t* ctx_lens,
+                                const int32_t* q_lens, const int32_t* q_offsets, int32_t* counts_dev,
+                                int32_t* counts_out, void* hip_stream) {
+  int rc = check_desc(desc, /*need_scales=*/false);
+  if (rc) return rc;
+  if (!counts_out) return ROLLATTN_EINVAL;
+  for (int i = 0; i < 4; ++i) counts_out[i] = 0;
+  if (desc->batch == 0) return ROLLATTN_OK;
+  if (!page_table || !ctx_lens || !counts_dev) return ROLLATTN_EINVAL;
+  if (!aligned16(page_table) || !aligned16(ctx_lens) || !aligned16(counts_dev) || (q_lens && !aligned16(q_lens)) ||
+      (q_offsets && !aligned16(q_offsets)))
+    return ROLLATTN_EALIGN;
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e = launch_check_inputs(page_table, ctx_lens, q_lens, q_offsets, desc->batch, desc->max_pages_per_seq,
+                                     desc->num_pages, counts_dev, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e == hipSuccess) e = hipMemcpy(counts_out, counts_dev, 4 * sizeof(int32_t), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail_hip(e);
+  return ROLLATTN_OK;
+}
+
 int rollattn_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_mu);
   g_profile = on != 0;

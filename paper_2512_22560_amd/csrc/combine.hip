@@ -101,7 +101,47 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(const unsigned char* p
   }
 }
 
+// Counts what the entry points take on trust (see rollattn_debug_check_inputs): one workgroup per trajectory.
+__global__ __launch_bounds__(kThreads) void check_inputs_kernel(const int32_t* page_table, const int32_t* ctx_lens,
+                                                                const int32_t* q_lens, const int32_t* q_offsets,
+                                                                int32_t batch, int32_t max_pages, int64_t num_pages,
+                                                                int32_t* counts) {
+  const int b = blockIdx.x;
+  const int len = ctx_lens[b];
+  const bool bad_len = len < 0 || (long)len > (long)max_pages * kPageSize;
+  const int live = bad_len ? 0 : (len + kPageSize - 1) / kPageSize;
+  int bad_ids = 0;
+  for (int pg = threadIdx.x; pg < live; pg += kThreads) {
+    const int id = page_table[(size_t)b * max_pages + pg];
+    bad_ids += (id < 0 || id >= num_pages) ? 1 : 0;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) bad_ids += __shfl_xor(bad_ids, off, 64);
+  if ((threadIdx.x & 63) == 0 && bad_ids) atomicAdd(counts + 1, bad_ids);
+  if (threadIdx.x == 0) {
+    if (bad_len) atomicAdd(counts + 0, 1);
+    if (q_lens) {
+      const int n = q_lens[b];
+      if (n < 0 || (!bad_len && n > len)) atomicAdd(counts + 2, 1);
+      if (q_offsets && (q_offsets[b + 1] - q_offsets[b] != n || (b == 0 && q_offsets[0] != 0))) atomicAdd(counts + 3, 1);
+    }
+  }
+}
+
+__global__ void clear4_kernel(int32_t* counts) {
+  if (threadIdx.x < 4) counts[threadIdx.x] = 0;
+}
+
 }  // namespace
+
+hipError_t launch_check_inputs(const int32_t* page_table, const int32_t* ctx_lens, const int32_t* q_lens,
+                               const int32_t* q_offsets, int32_t batch, int32_t max_pages, int64_t num_pages,
+                               int32_t* counts, hipStream_t s) {
+  hipLaunchKernelGGL(clear4_kernel, dim3(1), dim3(64), 0, s, counts);
+  hipLaunchKernelGGL(check_inputs_kernel, dim3(batch), dim3(kThreads), 0, s, page_table, ctx_lens, q_lens, q_offsets, batch,
+                     max_pages, num_pages, counts);
+  return hipGetLastError();
+}
 
 hipError_t launch_combine(const DecodeArgs& a, int head_dim, bool out_bf16, hipStream_t s) {
   const long rows = (long)a.batch * a.hq;

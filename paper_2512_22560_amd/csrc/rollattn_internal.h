@@ -102,6 +102,9 @@ hipError_t launch_shared_prep(const int32_t* ctx_lens, const int32_t* shared_len
                               int32_t* sfx_ctx, int32_t* sfx_table, hipStream_t s);
 hipError_t launch_shared_merge(const void* o1, const float* d1, const void* o2, const float* d2, void* out, long rows,
                                int head_dim, hipStream_t s);
+hipError_t launch_check_inputs(const int32_t* page_table, const int32_t* ctx_lens, const int32_t* q_lens,
+                               const int32_t* q_offsets, int32_t batch, int32_t max_pages, int64_t num_pages,
+                               int32_t* counts, hipStream_t s);
 hipError_t launch_gather(const void* pages, const int32_t* page_table, const int32_t* ctx_lens, int32_t b,
                          int32_t kv_head, int32_t hkv, int32_t max_pages, int32_t row_bytes, void* dst,
                          hipStream_t s);

@@ -85,6 +85,14 @@ def test_descriptor_errors_are_reported_before_any_launch():
     d = _desc(**bf)
     assert lib.rollattn_step_workspace_bytes(ctypes.byref(d), 8) >= (lib.rollattn_workspace_bytes(ctypes.byref(d), 8) + 256)
     assert lib.rollattn_step_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 8) == 0
+    counts = (ctypes.c_int32 * 4)(7, 7, 7, 7)
+    def check(d, table=fake, scratch=fake):
+        return lib.rollattn_debug_check_inputs(ctypes.byref(d), table, fake, None, None, scratch, counts, None)
+    assert check(_desc(batch=0)) == 0 and list(counts) == [0, 0, 0, 0]     # nothing to check
+    assert check(_desc(), table=None) == -1
+    assert check(_desc(), scratch=None) == -1
+    assert check(_desc(), scratch=ctypes.c_void_p(0x1004)) == -4
+    assert check(_desc(head_dim=96)) == -2
     for code in range(-6, 1):
         assert lib.rollattn_status_string(code)
     assert lib.rollattn_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 4) == 0

@@ -256,7 +256,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    B.lib()   # fail loudly if the HIP library is not built
+    if not os.path.exists(B.LIB_PATH):      # fresh checkout: build once; what is built is used as it is
+        import __graft_entry__
+        __graft_entry__.build()
+    B.lib()   # fails loudly if the HIP library still is not there
     dev = "cuda:0"
 
     if a.only == "copy":

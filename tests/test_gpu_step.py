@@ -105,3 +105,14 @@ def test_one_call_step_replays_from_a_graph_like_eager():
         _step(b, out=out, workspace=ws)
         torch.cuda.synchronize()
         assert torch.equal(got.view(torch.int16), out.view(torch.int16)), f"replay {it}"
+
+
+def test_mixed_step_on_a_batch_too_large_for_the_plans_lds_tables():
+    # 9000 trajectories: the decode plan keeps its scan in global memory, the append plan does not rank; both
+    # still have to tell decode rows from chunk rows
+    w = W.Workload("step_wide", 9000, 4, 2, 64, "bf16", "bf16", ("uniform", 1, 60), qlen=("uniform", 2, 20),
+                   append_rows=700, ctx_is_prefix=True, seed=W.BASE_SEED + 54)
+    b = W.build(w, DEV)
+    out = _step(b)
+    torch.cuda.synchronize()
+    check(out, oracle_append(b), "bf16", "9000 trajectories")

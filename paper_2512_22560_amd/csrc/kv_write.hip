@@ -1,6 +1,6 @@
 // KV write: the new tokens' K and V rows go into the paged cache, the step before attention.
 //
-// One workgroup per (trajectory, page that receives new tokens); the page belongs to that
+// One workgroup per (trajectory, page that receives new tokens, pool); the page belongs to that
 // trajectory alone, so nothing here needs an atomic.  Pools that store the source type take the
 // rows bit for bit, 16 bytes per lane.  FP8 pools keep one float scale per page and pool: the
 // workgroup takes the absolute maximum of the page's new rows (all heads), settles the scale
@@ -91,17 +91,30 @@ __global__ __launch_bounds__(kThreads) void kv_write_kernel(const KvWriteArgs a)
   const int chunks = slots * hkv * kChunksPerRow;        // per pool
   const size_t src_row0 = (size_t)(a.q_offsets[b] + lo - first);
 
-#pragma unroll 1
-  for (int pool = 0; pool < 2; ++pool) {
+  {
+    const int pool = blockIdx.z;                          // 0: K, 1: V -- the two pools have nothing in common
     const unsigned char* src = (const unsigned char*)(pool ? a.v_new : a.k_new) + src_row0 * hkv * D * SRC_BYTES;
     unsigned char* pages = (unsigned char*)(pool ? a.v_pages : a.k_pages);
     if constexpr (!FP8) {
       unsigned char* tile = pages + (size_t)phys * hkv * kPageSize * D * SRC_BYTES;
-      for (int c = threadIdx.x; c < chunks; c += kThreads) {
-        const int col = c % kChunksPerRow, rh = c / kChunksPerRow;     // source order: slot, head, chunk
-        const int h = rh % hkv, slot = rh / hkv;
-        const uintx4 v = *(const uintx4*)(src + (size_t)c * 16);
-        *(uintx4*)(tile + ((size_t)(h * kPageSize + s0 + slot) * D) * SRC_BYTES + col * 16) = v;
+      // four loads in flight per lane before the first store: the copy is all latency otherwise
+      constexpr int kBatch = 4;
+      for (int c0 = threadIdx.x; c0 < chunks; c0 += kBatch * kThreads) {
+        uintx4 v[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+          const int c = c0 + i * kThreads;
+          if (c < chunks) v[i] = *(const uintx4*)(src + (size_t)c * 16);
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+          const int c = c0 + i * kThreads;
+          if (c < chunks) {
+            const int col = c % kChunksPerRow, rh = c / kChunksPerRow;   // source order: slot, head, chunk
+            const int h = rh % hkv, slot = rh / hkv;
+            *(uintx4*)(tile + ((size_t)(h * kPageSize + s0 + slot) * D) * SRC_BYTES + col * 16) = v[i];
+          }
+        }
       }
     } else {
       static_assert(!FP8 || SRC_BYTES == 2, "FP8 pools are written from bf16 rows");
@@ -204,7 +217,7 @@ hipError_t launch_kv_write(const void* k_new, const void* v_new, const int32_t* 
                            int32_t max_q_len, int head_dim, int src_bytes, bool fp8, hipStream_t s) {
   KvWriteArgs a{k_new, v_new, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, k_scale, v_scale, hkv, max_pages};
   // a run of max_q_len tokens touches at most this many pages, wherever it starts
-  const dim3 grid((unsigned)((max_q_len + kPageSize - 1) / kPageSize + 1), (unsigned)batch);
+  const dim3 grid((unsigned)((max_q_len + kPageSize - 1) / kPageSize + 1), (unsigned)batch, 2);
   if (head_dim == 128) return launch_d<128>(a, src_bytes, fp8, grid, s);
   if (head_dim == 64) return launch_d<64>(a, src_bytes, fp8, grid, s);
   return hipErrorInvalidValue;

@@ -276,3 +276,49 @@ def test_non_positive_softmax_scale(scale):
                             k_scale=b.k_scale, v_scale=b.v_scale)
         ref = O.attn_decode(W.raw_numpy(b.q[: w.batch].contiguous()), **dict(oracle_args(b), sm_scale=scale))
         check(dec, ref, "bf16", f"decode scale {scale} {kvd}")
+
+
+@pytest.mark.parametrize("kvd", ["bf16", "fp8_e4m3"])
+@pytest.mark.parametrize("gain", [4.0, 100.0])
+def test_scores_that_keep_growing_along_the_context(kvd, gain):
+    # keys whose score rises with the position: the running reference of the online softmax has to move in
+    # almost every block, at gain 100 by more than 2^128 between blocks, so that exponentials taken against the
+    # stale reference overflow before the kernels notice (append) or would without the running maximum (decode)
+    import dataclasses
+    w = _wl("growing", 3, 8, 2, 128, "bf16", kvd, ("uniform", 500, 900), qlen=("uniform", 30, 200), seed=208, prefix=True)
+    b = W.build(w, DEV)
+    u = torch.nn.functional.normalize(torch.randn(128, generator=torch.Generator().manual_seed(2)), dim=0)
+    # every query is +u times gain * sqrt(D) (which the softmax scale 1/sqrt(D) takes back) and a per-row factor,
+    # key t of every trajectory is u * ramp(t) plus a little noise: score = gain * factor * t / 64
+    q = (u[None, None, :] * (gain * 128 ** 0.5) * (0.5 + torch.rand(b.q.shape[0], 8, 1, generator=torch.Generator().manual_seed(3)))).to(torch.bfloat16).to(DEV)
+    kp = b.k_pages
+    tbl = b.page_table.cpu().numpy()
+    ramp_pages = torch.zeros((b.num_pages, 16), dtype=torch.float32)
+    for bb in range(3):
+        n_pages = (int(b.ctx_lens_host[bb]) + 15) // 16
+        pos = torch.arange(n_pages * 16, dtype=torch.float32).reshape(n_pages, 16)
+        ramp_pages[torch.from_numpy(tbl[bb, :n_pages].astype(np.int64))] = pos / 64.0        # one unit per 64-token block
+    noise = 0.01 * torch.randn((b.num_pages, 2, 16, 128), generator=torch.Generator().manual_seed(4))
+    k_val = (ramp_pages[:, None, :, None] * u[None, None, None, :] + noise)                    # [pages, Hkv, 16, D]
+    if kvd == "bf16":
+        kp.copy_(k_val.to(torch.bfloat16))
+        b = dataclasses.replace(b, q=q)
+    else:
+        amax = k_val.abs().amax(dim=(1, 2, 3)).clamp_min(1e-6)
+        scale = (amax / 448.0).to(torch.float32)
+        codes = (k_val / scale[:, None, None, None]).to(torch.float8_e4m3fn).view(torch.uint8)
+        kp.copy_(codes)
+        b.k_scale.copy_(scale)
+        b = dataclasses.replace(b, q=q)
+    # the sharper the softmax, the closer a row comes to a single V row, whose elements reach |4|: the bar is
+    # stated for unit-scale outputs (bf16 rounding alone is 0.016 at 4), so both sides are scaled back to that
+    ref = oracle_append(b)
+    unit = max(1.0, float(np.abs(ref).max()))
+    check(gpu_append(b).float() / unit, ref / unit, "bf16", f"append, growing scores, gain {gain}")
+    offs = np.concatenate([[0], np.cumsum(b.q_lens_host)])
+    last = torch.from_numpy(offs[1:] - 1).to(DEV)
+    dec = dataclasses.replace(b, q=b.q[last].contiguous(), q_lens=torch.ones(3, dtype=torch.int32, device=DEV),
+                              q_offsets=torch.arange(4, dtype=torch.int32, device=DEV), q_lens_host=np.ones(3, dtype=np.int64))
+    ref = oracle_decode(dec)
+    unit = max(1.0, float(np.abs(ref).max()))
+    check(gpu_decode(dec).float() / unit, ref / unit, "bf16", f"decode, growing scores, gain {gain}")

@@ -177,6 +177,54 @@ def attn_decode(q, k_pages, v_pages, page_table, ctx_lens, *, sm_scale, q_dtype,
     return out
 
 
+def attn_lse(q, q_lens, k_pages, page_table, ctx_lens, *, sm_scale, q_dtype, kv_dtype, k_scale=None) -> np.ndarray:
+    """Base-2 logarithm of every row's softmax denominator, lse = log2 sum_t exp(z_t) over the tokens the row sees
+    (z_t = sm_scale <q, k_t>), float64 [rows, Hq]; -inf for a row that sees no token.  q_lens None: decode rows
+    (row b at position L_b - 1), else chunk rows as in attn_append.  It is what a caller needs, next to the
+    output, to merge attention over two disjoint token ranges (merge_states below): the engine's step over a
+    context that is split across calls, or across GPUs that each hold a slice of the pages."""
+    qf = decode_storage(q, q_dtype)
+    rows, hq, d = qf.shape
+    hkv = k_pages.shape[1]
+    group = hq // hkv
+    ctx_lens = np.asarray(ctx_lens, dtype=np.int64)
+    q_lens = np.ones(len(ctx_lens), dtype=np.int64) if q_lens is None else np.asarray(q_lens, dtype=np.int64)
+    scale = np.float64(np.float32(sm_scale))
+    lse = np.full((rows, hq), -np.inf, dtype=np.float64)
+    row0 = 0
+    for b in range(len(ctx_lens)):
+        n, length = int(q_lens[b]), int(ctx_lens[b])
+        for g in range(hkv):
+            k = gather_tokens(k_pages, page_table, b, g, length, kv_dtype, k_scale)
+            for i in range(n):
+                seen = length - n + i + 1                   # tokens [0, seen) are visible to chunk row i
+                if seen <= 0:
+                    continue
+                for h in range(g * group, (g + 1) * group):
+                    z = scale * (k[:seen] @ qf[row0 + i, h, :])
+                    top = z.max()
+                    lse[row0 + i, h] = (top + np.log(np.exp(z - top).sum())) / np.log(2.0)
+        row0 += n
+    return lse
+
+
+def merge_states(o1, lse1, o2, lse2):
+    """Attention over the union of two disjoint token ranges from the results over each: with weights
+    w_i = 2^lse_i the output is (w_1 o_1 + w_2 o_2) / (w_1 + w_2) and the denominator's logarithm
+    log2(w_1 + w_2); a side that saw nothing (lse = -inf) has weight 0, and rows where both saw nothing give
+    zeros and -inf.  o [rows, Hq, D], lse [rows, Hq]; returns (o, lse) in float64."""
+    o1, o2 = np.asarray(o1, dtype=np.float64), np.asarray(o2, dtype=np.float64)
+    l1, l2 = np.asarray(lse1, dtype=np.float64), np.asarray(lse2, dtype=np.float64)
+    top = np.maximum(l1, l2)
+    safe = np.where(np.isfinite(top), top, 0.0)
+    w1, w2 = np.exp2(l1 - safe), np.exp2(l2 - safe)        # exp2(-inf) = 0
+    tot = w1 + w2
+    with np.errstate(divide="ignore", invalid="ignore"):
+        o = np.where(tot[..., None] > 0, (w1[..., None] * o1 + w2[..., None] * o2) / tot[..., None], 0.0)
+        lse = np.where(tot > 0, safe + np.log2(tot), -np.inf)
+    return o, lse
+
+
 def partial_softmax_attention(q_row, k, v, sm_scale):
     """Attention of one query over one slice of tokens, returned as the triple the
     split-K partition exchanges: (m, l, o) with m the slice's largest score, l the

@@ -385,3 +385,74 @@ def test_split_plan_covers_every_block_once_in_equal_runs():
                     assert whole                                    # only the ends of a run can be partial
         assert sorted(by_worker) == list(range(len(by_worker)))     # workers are used in order
         assert all(starts[w][0] == -1 for w in range(len(by_worker), workers))
+
+
+# ---------------------------------------------------------------- softmax denominators and the merge of two ranges
+
+def _lse_single(q, k, **kw):
+    L, D = k.shape
+    n_pages = (L + 15) // 16
+    kp = np.full((n_pages, 1, 16, D), np.nan, dtype=np.float32)
+    kp.reshape(-1, D)[:L] = k
+    table = np.arange(n_pages, dtype=np.int32)[None, :]
+    return O.attn_lse(q.reshape(1, 1, D).astype(np.float32), None, kp, table, np.array([L]), sm_scale=kw.get("sm_scale", 1.0),
+                      q_dtype="f32", kv_dtype="f32")[0, 0]
+
+
+def test_lse_closed_forms():
+    rng = np.random.default_rng(60)
+    q, k = rng.standard_normal(8).astype(np.float32), rng.standard_normal((1, 8)).astype(np.float32)
+    z = float(np.float64(np.float32(0.37)) * (np.float64(k[0]) @ np.float64(q)))
+    assert abs(_lse_single(q, k, sm_scale=0.37) - z * math.log2(math.e)) < 1e-12          # one key: log2 exp(z)
+    for L in (2, 17, 100):                                                                 # L equal keys: + log2 L
+        assert abs(_lse_single(q, np.repeat(k, L, axis=0), sm_scale=0.37) - (z * math.log2(math.e) + math.log2(L))) < 1e-12
+
+
+def test_lse_matches_library_logsumexp_with_causal_rows():
+    from scipy.special import logsumexp
+    b = tiny(batch=3, hq=4, hkv=2, d=16, ctx=("uniform", 20, 90), qlen=("uniform", 0, 9), seed=61, ctx_is_prefix=True)
+    args = oracle_args(b)
+    q = W.raw_numpy(b.q)
+    got = O.attn_lse(q, b.q_lens_host, args["k_pages"], args["page_table"], args["ctx_lens"], sm_scale=args["sm_scale"],
+                     q_dtype="f32", kv_dtype="f32")
+    row = 0
+    for bb in range(3):
+        n, L = int(b.q_lens_host[bb]), int(b.ctx_lens_host[bb])
+        for i in range(n):
+            for h in range(4):
+                k = O.gather_tokens(args["k_pages"], args["page_table"], bb, h // 2, L, "f32")
+                z = [float(np.float64(np.float32(args["sm_scale"])) * sum(float(k[t, e]) * float(q[row, h, e]) for e in range(16)))
+                     for t in range(L - n + i + 1)]                                        # scores by plain loops
+                assert abs(got[row, h] - logsumexp(z) / math.log(2.0)) < 1e-10
+            row += 1
+    assert row == got.shape[0]
+
+
+def test_merging_two_ranges_equals_attention_over_their_union():
+    b = tiny(batch=4, hq=4, hkv=2, d=16, ctx=("uniform", 40, 200), seed=62)
+    args = oracle_args(b)
+    q = W.raw_numpy(b.q)
+    whole = O.attn_decode(q, **args)
+    lse_args = dict(sm_scale=args["sm_scale"], q_dtype="f32", kv_dtype="f32")
+    whole_lse = O.attn_lse(q, None, args["k_pages"], args["page_table"], args["ctx_lens"], **lse_args)
+    # range 1: the first S_b tokens (whole pages); range 2: the rest, through a table shifted by S_b / 16 entries
+    cut = np.array([16, 32, 0, 48])
+    table = args["page_table"]
+    shifted = np.zeros_like(table)
+    for bb in range(4):
+        shifted[bb, :table.shape[1] - cut[bb] // 16] = table[bb, cut[bb] // 16:]
+    a1 = dict(args, ctx_lens=cut)
+    a2 = dict(args, ctx_lens=b.ctx_lens_host - cut, page_table=shifted)
+    o1, o2 = O.attn_decode(q, **a1), O.attn_decode(q, **a2)
+    l1 = O.attn_lse(q, None, a1["k_pages"], a1["page_table"], a1["ctx_lens"], **lse_args)
+    l2 = O.attn_lse(q, None, a2["k_pages"], a2["page_table"], a2["ctx_lens"], **lse_args)
+    assert np.all(np.isneginf(l1[2])) and np.all(o1[2] == 0)                               # an empty range: weight 0
+    o, lse = O.merge_states(o1, l1, o2, l2)
+    np.testing.assert_allclose(o, whole, atol=1e-12)
+    np.testing.assert_allclose(lse, whole_lse, atol=1e-12)
+    # both sides empty: zeros and -inf; merging is symmetric
+    o0, l0 = O.merge_states(o1[2:3], l1[2:3], o1[2:3], l1[2:3])
+    assert np.all(o0 == 0) and np.all(np.isneginf(l0))
+    o_sw, l_sw = O.merge_states(o2, l2, o1, l1)
+    np.testing.assert_allclose(o_sw, o, atol=1e-15)
+    np.testing.assert_allclose(l_sw, lse, atol=1e-15)

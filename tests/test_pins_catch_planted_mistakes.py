@@ -32,6 +32,15 @@ ATTENTION = ("attention.py", "tests/test_oracle_pins.py", [
     ("E4M3: subnormal exponent", "subnormal = (m / 8.0) * 2.0 ** (-6)", "subnormal = (m / 8.0) * 2.0 ** (-7)"),
     ("decode: sign of the exponent", "w = np.exp(z - z.max())", "w = np.exp(z.max() - z)"),
     ("merge: partial sums not weighted", "a = np.exp(ms - ms.max()) * ls", "a = np.exp(ms - ms.max())"),
+    ("lse: natural logarithm", "lse[row0 + i, h] = (top + np.log(np.exp(z - top).sum())) / np.log(2.0)",
+     "lse[row0 + i, h] = (top + np.log(np.exp(z - top).sum()))"),
+    ("lse: chunk row sees one token too many", "seen = length - n + i + 1 ", "seen = min(length, length - n + i + 2) "),
+    ("lse: maximum left out", "lse[row0 + i, h] = (top + np.log(np.exp(z - top).sum())) / np.log(2.0)",
+     "lse[row0 + i, h] = (np.log(np.exp(z - top).sum())) / np.log(2.0)"),
+    ("merge of ranges: weights e^lse", "w1, w2 = np.exp2(l1 - safe), np.exp2(l2 - safe)", "w1, w2 = np.exp(l1 - safe), np.exp(l2 - safe)"),
+    ("merge of ranges: denominator without the reference", "lse = np.where(tot > 0, safe + np.log2(tot), -np.inf)",
+     "lse = np.where(tot > 0, np.log2(tot), -np.inf)"),
+    ("merge of ranges: plain average", "(w1[..., None] * o1 + w2[..., None] * o2) / tot[..., None]", "(o1 + o2) / 2"),
 ])
 
 KV_WRITE = ("kv_write.py", "tests/test_kv_write_pins.py", [

@@ -113,6 +113,28 @@ int attn_append(const rollattn_desc *desc, const void *q_chunk, const int32_t *q
                 const void *v_pages, const int32_t *page_table, const int32_t *ctx_lens, void *out,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same two calls with one more output, lse [rows][Hq] float (device): the base-2 logarithm of every row's
+ * softmax denominator, log2 sum_t exp(sm_scale <q, k_t>) over the tokens the row sees; -inf for a row that sees
+ * none.  Next to `out` it is what merges attention over two disjoint token ranges (attn_merge): a context whose
+ * pages are split across calls, or across GPUs that each hold a slice of them -- every multi-turn trajectory
+ * keeps growing (Section 2.1), and the longest ones are the ones a single cache cannot hold. */
+int attn_decode_lse(const rollattn_desc *desc, const void *q, const void *k_pages, const void *v_pages,
+                    const int32_t *page_table, const int32_t *ctx_lens, void *out, float *lse, void *workspace,
+                    size_t workspace_bytes, void *hip_stream);
+int attn_append_lse(const rollattn_desc *desc, const void *q_chunk, const int32_t *q_lens,
+                    const int32_t *q_offsets, int32_t total_q, int32_t max_q_len, const void *k_pages,
+                    const void *v_pages, const int32_t *page_table, const int32_t *ctx_lens, void *out,
+                    float *lse, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Merge of two results over disjoint token ranges, row by row: with w_i = 2^lse_i,
+ *   out = (w_1 o_1 + w_2 o_2) / (w_1 + w_2),   lse_out = log2(w_1 + w_2)   (lse_out may be NULL)
+ * which is the attention over the union of the ranges.  A side with lse = -inf has weight 0 (its o is not
+ * looked at); where both are -inf the row is zero and lse_out -inf.  o_1, o_2, out: [rows][Hq][D] of
+ * desc->q_dtype (only num_q_heads, head_dim and q_dtype of desc are used besides the usual checks), lse:
+ * [rows][Hq] float.  out may alias o_1 or o_2.  No workspace. */
+int attn_merge(const rollattn_desc *desc, int64_t rows, const void *o1, const float *lse1, const void *o2,
+               const float *lse2, void *out, float *lse_out, void *hip_stream);
+
 /* One engine step on a mixed batch in one call: during a rollout some requests of the batch generate (one new
  * token) while others have just received an observation and prefill it (Section 6.1, the inference worker takes
  * a decode or a prefill step per request; Section 3.1, the two phases).  Arguments as attn_append, with the

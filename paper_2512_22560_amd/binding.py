@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "librollattn.so")
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
 EXPORTS = (
-    "attn_decode", "attn_append", "attn_step", "attn_decode_shared", "kv_write", "rollattn_workspace_bytes",
+    "attn_decode", "attn_append", "attn_decode_lse", "attn_append_lse", "attn_merge", "attn_step", "attn_decode_shared",
+    "kv_write", "rollattn_workspace_bytes",
     "rollattn_step_workspace_bytes", "rollattn_shared_workspace_bytes", "rollattn_debug_gather",
     "rollattn_debug_check_inputs",
     "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan",
@@ -64,6 +65,12 @@ def lib() -> ctypes.CDLL:
         l.attn_decode.restype = ctypes.c_int
         l.attn_append.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         l.attn_append.restype = ctypes.c_int
+        l.attn_decode_lse.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        l.attn_decode_lse.restype = ctypes.c_int
+        l.attn_append_lse.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        l.attn_append_lse.restype = ctypes.c_int
+        l.attn_merge.argtypes = [dp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp]
+        l.attn_merge.restype = ctypes.c_int
         l.attn_step.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         l.attn_step.restype = ctypes.c_int
         l.rollattn_step_workspace_bytes.argtypes = [dp, i32]
@@ -183,6 +190,61 @@ def attn_append(q_chunk, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_le
     if rc:
         raise RollattnError(rc, "attn_append")
     return out
+
+
+def attn_decode_lse(q, k_pages, v_pages, page_table, ctx_lens, *, sm_scale, k_scale=None, v_scale=None,
+                    out=None, lse=None, workspace=None, stream=None):
+    """attn_decode plus lse [B, Hq] float32: log2 of every row's softmax denominator (-inf for an empty context)."""
+    _check_contig(q, k_pages, v_pages, page_table, ctx_lens, k_scale, v_scale, out, lse)
+    desc = make_desc(q, k_pages, page_table, sm_scale=sm_scale, k_scale=k_scale, v_scale=v_scale)
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, q.shape[0], q.device)
+    rc = lib().attn_decode_lse(ctypes.byref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(page_table), _ptr(ctx_lens),
+                               _ptr(out), _ptr(lse), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "attn_decode_lse")
+    return out, lse
+
+
+def attn_append_lse(q_chunk, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, *, sm_scale, max_q_len,
+                    k_scale=None, v_scale=None, out=None, lse=None, workspace=None, stream=None):
+    """attn_append plus lse [total_q, Hq] float32."""
+    _check_contig(q_chunk, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, k_scale, v_scale, out, lse)
+    desc = make_desc(q_chunk, k_pages, page_table, sm_scale=sm_scale, k_scale=k_scale, v_scale=v_scale)
+    total_q = int(q_chunk.shape[0])
+    if out is None:
+        out = torch.empty_like(q_chunk)
+    if lse is None:
+        lse = torch.empty(q_chunk.shape[:2], dtype=torch.float32, device=q_chunk.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, total_q, q_chunk.device)
+    rc = lib().attn_append_lse(ctypes.byref(desc), _ptr(q_chunk), _ptr(q_lens), _ptr(q_offsets), total_q, int(max_q_len),
+                               _ptr(k_pages), _ptr(v_pages), _ptr(page_table), _ptr(ctx_lens), _ptr(out), _ptr(lse),
+                               _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "attn_append_lse")
+    return out, lse
+
+
+def attn_merge(o1, lse1, o2, lse2, *, out=None, lse_out=None, stream=None):
+    """Attention over the union of two disjoint token ranges from (o, lse) over each; returns (out, lse_out)."""
+    _check_contig(o1, lse1, o2, lse2, out, lse_out)
+    rows, hq, d = o1.shape
+    desc = Desc(batch=0, num_q_heads=int(hq), num_kv_heads=int(hq), head_dim=int(d), page_size=16, max_pages_per_seq=1,
+                num_pages=0, q_dtype=_dtype_code(o1), kv_dtype=_dtype_code(o1), sm_scale=1.0, k_scale=None, v_scale=None)
+    if out is None:
+        out = torch.empty_like(o1)
+    if lse_out is None:
+        lse_out = torch.empty_like(lse1)
+    rc = lib().attn_merge(ctypes.byref(desc), int(rows), _ptr(o1), _ptr(lse1), _ptr(o2), _ptr(lse2), _ptr(out), _ptr(lse_out),
+                          _stream(stream))
+    if rc:
+        raise RollattnError(rc, "attn_merge")
+    return out, lse_out
 
 
 def attn_step(q, q_lens, q_offsets, k_pages, v_pages, page_table, ctx_lens, *, sm_scale, max_q_len,

@@ -299,7 +299,7 @@ int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, c
 
 // attn_append proper.  table_stride: int32 entries between the page-table rows of consecutive
 // trajectories; noncausal: every row sees all of [0, L_b) (then n_b <= L_b is not required);
-// lse as in decode_impl, [total_q][Hq].  Both extras are for the bf16 kernels only.
+// lse as in decode_impl, [total_q][Hq].  table_stride and noncausal are for the bf16 kernels only.
 static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int32_t* q_lens, const int32_t* q_offsets,
                        int32_t total_q, int32_t max_q_len, const void* k_pages, const void* v_pages,
                        const int32_t* page_table, const int32_t* ctx_lens, void* out, void* workspace,
@@ -365,6 +365,42 @@ int attn_append(const rollattn_desc* desc, const void* q_chunk, const int32_t* q
   if (!desc) return ROLLATTN_EINVAL;
   return append_impl(desc, q_chunk, q_lens, q_offsets, total_q, max_q_len, k_pages, v_pages, page_table, ctx_lens, out,
                      workspace, workspace_bytes, hip_stream, desc->max_pages_per_seq, false, nullptr);
+}
+
+int attn_decode_lse(const rollattn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                    const int32_t* page_table, const int32_t* ctx_lens, void* out, float* lse, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  if (desc && desc->batch > 0 && !lse) return ROLLATTN_EINVAL;
+  if (lse && !aligned16(lse)) return ROLLATTN_EALIGN;
+  return decode_impl(desc, q, k_pages, v_pages, page_table, ctx_lens, out, workspace, workspace_bytes, hip_stream, lse);
+}
+
+int attn_append_lse(const rollattn_desc* desc, const void* q_chunk, const int32_t* q_lens, const int32_t* q_offsets,
+                    int32_t total_q, int32_t max_q_len, const void* k_pages, const void* v_pages,
+                    const int32_t* page_table, const int32_t* ctx_lens, void* out, float* lse, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  if (!desc) return ROLLATTN_EINVAL;
+  if (desc->batch > 0 && total_q > 0 && !lse) return ROLLATTN_EINVAL;
+  if (lse && !aligned16(lse)) return ROLLATTN_EALIGN;
+  return append_impl(desc, q_chunk, q_lens, q_offsets, total_q, max_q_len, k_pages, v_pages, page_table, ctx_lens, out,
+                     workspace, workspace_bytes, hip_stream, desc->max_pages_per_seq, false, lse);
+}
+
+int attn_merge(const rollattn_desc* desc, int64_t rows, const void* o1, const float* lse1, const void* o2,
+               const float* lse2, void* out, float* lse_out, void* hip_stream) {
+  int rc = check_desc(desc, /*need_scales=*/false);
+  if (rc) return rc;
+  if (rows < 0) return ROLLATTN_EINVAL;
+  if (rows == 0) return ROLLATTN_OK;
+  if (!o1 || !lse1 || !o2 || !lse2 || !out) return ROLLATTN_EINVAL;
+  if (!aligned16(o1) || !aligned16(lse1) || !aligned16(o2) || !aligned16(lse2) || !aligned16(out) ||
+      (lse_out && !aligned16(lse_out)))
+    return ROLLATTN_EALIGN;
+  if (rows * (int64_t)desc->num_q_heads > (int64_t)INT32_MAX * 4) return ROLLATTN_ESHAPE;   // one wave per (row, head), four per workgroup
+  const hipError_t e = launch_merge_states(o1, lse1, o2, lse2, out, lse_out, (long)rows * desc->num_q_heads, desc->head_dim,
+                                           desc->q_dtype == ROLLATTN_F32, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail_hip(e);
+  return ROLLATTN_OK;
 }
 
 size_t rollattn_step_workspace_bytes(const rollattn_desc* desc, int32_t total_q) {
@@ -476,8 +512,8 @@ int attn_decode_shared(const rollattn_desc* desc, const void* q, const void* k_p
   rc = decode_impl(desc, q, k_pages, v_pages, sfx_table, sfx_ctx, base + L.o2, base + L.dec_ws, L.dec_bytes, hip_stream,
                    (float*)(base + L.d2));
   if (rc) return rc;
-  e = launch_shared_merge(base + L.o1, (const float*)(base + L.d1), base + L.o2, (const float*)(base + L.d2), out,
-                          (long)desc->batch * desc->num_q_heads, desc->head_dim, s);
+  e = launch_merge_states(base + L.o1, (const float*)(base + L.d1), base + L.o2, (const float*)(base + L.d2), out, nullptr,
+                          (long)desc->batch * desc->num_q_heads, desc->head_dim, /*f32=*/false, s);
   if (e != hipSuccess) return fail_hip(e);
   return ROLLATTN_OK;
 }

@@ -135,7 +135,9 @@ __global__ __launch_bounds__(kThreads) void decode_f32_kernel(const DecodeArgs a
     for (int e = tid; e < n_heads * D; e += kThreads) {
       const int h = e / D, d = e % D;
       if (whole) {
-        ((float*)a.out)[((size_t)b * a.hq + (size_t)g * group + h0 + h) * D + d] = o_out[h][d] / ml_out[h][1];
+        const size_t orow = (size_t)b * a.hq + (size_t)g * group + h0 + h;
+        ((float*)a.out)[orow * D + d] = o_out[h][d] / ml_out[h][1];
+        if (a.lse && d == 0) a.lse[orow] = ml_out[h][0] + __builtin_amdgcn_logf(ml_out[h][1]);
       } else {
         const size_t slot = (size_t)worker * 2 + (first_segment ? 0 : 1);
         a.partial_o[(slot * kHT + h) * D + d] = o_out[h][d];
@@ -197,7 +199,9 @@ __global__ __launch_bounds__(kThreads) void append_f32_kernel(const AppendArgs a
                   ml_out);
     for (int e = tid; e < n_heads * D; e += kThreads) {
       const int h = e / D, d = e % D;
-      ((float*)a.out)[((size_t)row * a.hq + (size_t)g * group + h0 + h) * D + d] = o_out[h][d] / ml_out[h][1];
+      const size_t orow = (size_t)row * a.hq + (size_t)g * group + h0 + h;
+      ((float*)a.out)[orow * D + d] = o_out[h][d] / ml_out[h][1];
+      if (a.lse && d == 0) a.lse[orow] = ml_out[h][0] + __builtin_amdgcn_logf(ml_out[h][1]);
     }
     __syncthreads();
   }

@@ -100,8 +100,8 @@ hipError_t launch_kv_write(const void* k_new, const void* v_new, const int32_t* 
 hipError_t launch_shared_prep(const int32_t* ctx_lens, const int32_t* shared_lens, const int32_t* page_table, int32_t batch,
                               int32_t group_size, int32_t max_pages, int32_t* grp_ctx, int32_t* grp_qlens, int32_t* grp_qoff,
                               int32_t* sfx_ctx, int32_t* sfx_table, hipStream_t s);
-hipError_t launch_shared_merge(const void* o1, const float* d1, const void* o2, const float* d2, void* out, long rows,
-                               int head_dim, hipStream_t s);
+hipError_t launch_merge_states(const void* o1, const float* d1, const void* o2, const float* d2, void* out, float* d_out,
+                               long rows, int head_dim, bool f32, hipStream_t s);
 hipError_t launch_check_inputs(const int32_t* page_table, const int32_t* ctx_lens, const int32_t* q_lens,
                                const int32_t* q_offsets, int32_t batch, int32_t max_pages, int64_t num_pages,
                                int32_t* counts, hipStream_t s);

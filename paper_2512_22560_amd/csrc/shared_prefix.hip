@@ -47,21 +47,32 @@ __global__ __launch_bounds__(kThreads) void shared_prep_kernel(const int32_t* __
     sfx_table[(size_t)b * max_pages + p] = (p + shift < live) ? page_table[(size_t)b * max_pages + p + shift] : -1;
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads) void shared_merge_kernel(const __bf16* __restrict__ o1, const float* __restrict__ d1,
-                                                                const __bf16* __restrict__ o2, const float* __restrict__ d2,
-                                                                __bf16* __restrict__ out, long rows) {
+// Attention over the union of two disjoint token ranges from the results over each (one wave per row): weights
+// 2^d1 and 2^d2 on the two outputs, log2(2^d1 + 2^d2) as the new denominator's logarithm.  A side that saw nothing
+// (d = -inf) has weight 0; when both saw nothing the row is zero and its logarithm -inf.
+template <int D, typename T>
+__global__ __launch_bounds__(kThreads) void merge_states_kernel(const T* __restrict__ o1, const float* __restrict__ d1,
+                                                                const T* __restrict__ o2, const float* __restrict__ d2,
+                                                                T* __restrict__ out, float* __restrict__ d_out, long rows) {
   constexpr int kPer = D / 64;
   const int lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
   if (row >= rows) return;
   const float a = d1[row], b = d2[row];
-  const float m = fmaxf(a, b);                        // the private half is never empty, so m is finite
-  const float wa = __builtin_amdgcn_exp2f(a - m), wb = __builtin_amdgcn_exp2f(b - m);
-  const float inv = 1.f / (wa + wb);
+  const float top = fmaxf(a, b);
+  const float m = (top == -INFINITY) ? 0.f : top;
+  const float wa = __builtin_amdgcn_exp2f(a - m), wb = __builtin_amdgcn_exp2f(b - m);   // 2^-inf = 0
+  const float tot = wa + wb;
+  const float inv = tot > 0.f ? 1.f / tot : 0.f;
   const size_t off = (size_t)row * D + lane * kPer;
 #pragma unroll
-  for (int e = 0; e < kPer; ++e) out[off + e] = (__bf16)((wa * (float)o1[off + e] + wb * (float)o2[off + e]) * inv);
+  for (int e = 0; e < kPer; ++e) {
+    // an empty side may hold anything (zeros by this library's calls): its weight is an exact zero, but keep
+    // non-finite leftovers of other producers out of the sum
+    const float x1 = wa > 0.f ? (float)o1[off + e] : 0.f, x2 = wb > 0.f ? (float)o2[off + e] : 0.f;
+    out[off + e] = (T)((wa * x1 + wb * x2) * inv);
+  }
+  if (d_out && lane == 0) d_out[row] = tot > 0.f ? m + __builtin_amdgcn_logf(tot) : -INFINITY;
 }
 
 }  // namespace
@@ -74,14 +85,18 @@ hipError_t launch_shared_prep(const int32_t* ctx_lens, const int32_t* shared_len
   return hipGetLastError();
 }
 
-hipError_t launch_shared_merge(const void* o1, const float* d1, const void* o2, const float* d2, void* out, long rows,
-                               int head_dim, hipStream_t s) {
+hipError_t launch_merge_states(const void* o1, const float* d1, const void* o2, const float* d2, void* out, float* d_out,
+                               long rows, int head_dim, bool f32, hipStream_t s) {
   const int grid = (int)((rows + kThreads / 64 - 1) / (kThreads / 64));
   if (grid == 0) return hipSuccess;
-  if (head_dim == 128) {
-    hipLaunchKernelGGL((shared_merge_kernel<128>), dim3(grid), dim3(kThreads), 0, s, (const __bf16*)o1, d1, (const __bf16*)o2, d2, (__bf16*)out, rows);
+  if (head_dim == 128 && !f32) {
+    hipLaunchKernelGGL((merge_states_kernel<128, __bf16>), dim3(grid), dim3(kThreads), 0, s, (const __bf16*)o1, d1, (const __bf16*)o2, d2, (__bf16*)out, d_out, rows);
+  } else if (head_dim == 64 && !f32) {
+    hipLaunchKernelGGL((merge_states_kernel<64, __bf16>), dim3(grid), dim3(kThreads), 0, s, (const __bf16*)o1, d1, (const __bf16*)o2, d2, (__bf16*)out, d_out, rows);
+  } else if (head_dim == 128) {
+    hipLaunchKernelGGL((merge_states_kernel<128, float>), dim3(grid), dim3(kThreads), 0, s, (const float*)o1, d1, (const float*)o2, d2, (float*)out, d_out, rows);
   } else if (head_dim == 64) {
-    hipLaunchKernelGGL((shared_merge_kernel<64>), dim3(grid), dim3(kThreads), 0, s, (const __bf16*)o1, d1, (const __bf16*)o2, d2, (__bf16*)out, rows);
+    hipLaunchKernelGGL((merge_states_kernel<64, float>), dim3(grid), dim3(kThreads), 0, s, (const float*)o1, d1, (const float*)o2, d2, (float*)out, d_out, rows);
   } else {
     return hipErrorInvalidValue;
   }

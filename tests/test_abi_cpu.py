@@ -85,6 +85,19 @@ def test_descriptor_errors_are_reported_before_any_launch():
     d = _desc(**bf)
     assert lib.rollattn_step_workspace_bytes(ctypes.byref(d), 8) >= (lib.rollattn_workspace_bytes(ctypes.byref(d), 8) + 256)
     assert lib.rollattn_step_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 8) == 0
+    assert lib.attn_decode_lse(ctypes.byref(_desc()), fake, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == -1   # no lse buffer
+    assert lib.attn_decode_lse(ctypes.byref(_desc()), fake, fake, fake, fake, fake, fake, ctypes.c_void_p(0x1004), fake, 1 << 40, None) == -4
+    assert lib.attn_decode_lse(ctypes.byref(_desc(batch=0)), fake, fake, fake, fake, fake, fake, None, fake, 0, None) == 0
+    assert lib.attn_append_lse(ctypes.byref(_desc()), fake, fake, fake, 8, 2, fake, fake, fake, fake, fake, None, fake, 1 << 40, None) == -1
+    assert lib.attn_append_lse(ctypes.byref(_desc()), fake, fake, fake, 0, 0, fake, fake, fake, fake, fake, None, fake, 0, None) == 0
+    def merge(d, rows=5, o1=fake, l2=fake, lo=fake):
+        return lib.attn_merge(ctypes.byref(d), rows, o1, fake, fake, l2, fake, lo, None)
+    assert merge(_desc(), rows=0) == 0
+    assert merge(_desc(), rows=-1) == -1
+    assert merge(_desc(), o1=None) == -1
+    assert merge(_desc(), l2=ctypes.c_void_p(0x1008)) == -4
+    assert merge(_desc(), lo=ctypes.c_void_p(0x1008)) == -4
+    assert merge(_desc(head_dim=96)) == -2
     counts = (ctypes.c_int32 * 4)(7, 7, 7, 7)
     def check(d, table=fake, scratch=fake):
         return lib.rollattn_debug_check_inputs(ctypes.byref(d), table, fake, None, None, scratch, counts, None)

@@ -51,27 +51,30 @@ __global__ __launch_bounds__(kThreads) void shared_prep_kernel(const int32_t* __
 // 2^d1 and 2^d2 on the two outputs, log2(2^d1 + 2^d2) as the new denominator's logarithm.  A side that saw nothing
 // (d = -inf) has weight 0; when both saw nothing the row is zero and its logarithm -inf.
 template <int D, typename T>
-__global__ __launch_bounds__(kThreads) void merge_states_kernel(const T* __restrict__ o1, const float* __restrict__ d1,
-                                                                const T* __restrict__ o2, const float* __restrict__ d2,
-                                                                T* __restrict__ out, float* __restrict__ d_out, long rows) {
-  constexpr int kPer = D / 64;
+__global__ __launch_bounds__(kThreads) void merge_states_kernel(const T* o1, const float* __restrict__ d1, const T* o2,
+                                                                const float* __restrict__ d2, T* out, float* d_out, long rows) {
+  constexpr int kPer = D / 64;                            // consecutive elements per lane, moved as one vector
+  typedef T vec_t __attribute__((ext_vector_type(kPer)));
   const int lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
   if (row >= rows) return;
+  const size_t off = (size_t)row * D + lane * kPer;
+  const vec_t v1 = *(const vec_t*)(o1 + off), v2 = *(const vec_t*)(o2 + off);   // out may be o1 or o2: read first
   const float a = d1[row], b = d2[row];
   const float top = fmaxf(a, b);
   const float m = (top == -INFINITY) ? 0.f : top;
   const float wa = __builtin_amdgcn_exp2f(a - m), wb = __builtin_amdgcn_exp2f(b - m);   // 2^-inf = 0
   const float tot = wa + wb;
   const float inv = tot > 0.f ? 1.f / tot : 0.f;
-  const size_t off = (size_t)row * D + lane * kPer;
+  vec_t r;
 #pragma unroll
   for (int e = 0; e < kPer; ++e) {
     // an empty side may hold anything (zeros by this library's calls): its weight is an exact zero, but keep
     // non-finite leftovers of other producers out of the sum
-    const float x1 = wa > 0.f ? (float)o1[off + e] : 0.f, x2 = wb > 0.f ? (float)o2[off + e] : 0.f;
-    out[off + e] = (T)((wa * x1 + wb * x2) * inv);
+    const float x1 = wa > 0.f ? (float)v1[e] : 0.f, x2 = wb > 0.f ? (float)v2[e] : 0.f;
+    r[e] = (T)((wa * x1 + wb * x2) * inv);
   }
+  *(vec_t*)(out + off) = r;
   if (d_out && lane == 0) d_out[row] = tot > 0.f ? m + __builtin_amdgcn_logf(tot) : -INFINITY;
 }
 

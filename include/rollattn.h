@@ -71,7 +71,9 @@ typedef enum {
   ROLLATTN_EDTYPE = -3,     /* unsupported q/kv type pair, FP8 without scales          */
   ROLLATTN_EALIGN = -4,     /* a device pointer is not 16-byte aligned                 */
   ROLLATTN_EWORKSPACE = -5, /* workspace smaller than rollattn_workspace_bytes()       */
-  ROLLATTN_EHIP = -6        /* a HIP call failed; text via rollattn_last_hip_error()   */
+  ROLLATTN_EHIP = -6,       /* a HIP call failed; text via rollattn_last_hip_error()   */
+  ROLLATTN_ELIMIT = -7      /* attn_decode_static: the batch needs more scratch than the
+                               built-in array of rollattn_static_scratch_bytes() holds */
 } rollattn_status;
 
 typedef struct {
@@ -100,6 +102,23 @@ typedef struct {
 int attn_decode(const rollattn_desc *desc, const void *q, const void *k_pages, const void *v_pages,
                 const int32_t *page_table, const int32_t *ctx_lens, void *out, void *workspace,
                 size_t workspace_bytes, void *hip_stream);
+
+/* attn_decode for callers that cannot allocate device memory or carry a workspace around: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit for bit
+ * the same result as attn_decode, but the plan and the split partials live in an array that is part of the
+ * library's code object (rollattn_static_scratch_bytes() = 36 MiB, held by every GPU the library runs on until
+ * the process ends) instead of a caller's workspace.  The call allocates and frees nothing.  A descriptor whose
+ * decode workspace (rollattn_workspace_bytes(desc, batch), which grows by 4 bytes per trajectory) exceeds the
+ * array is refused with ROLLATTN_ELIMIT before anything is launched: BF16/FP8 D = 128 fits up to about 800,000
+ * trajectories.  Every call on a GPU uses that GPU's one array and nothing in it needs clearing between calls
+ * (each call rewrites the plan and every partial it reads), so calls on one GPU must be ordered on one stream or
+ * otherwise serialised: two that overlap race.  The array's device address is looked up on the first call on each
+ * device (hipGetSymbolAddress, no allocation); rollattn_static_init() does that lookup for the current device
+ * ahead of time, e.g. before a stream capture begins. */
+int attn_decode_static(const rollattn_desc *desc, const void *q, const void *k_pages, const void *v_pages,
+                       const int32_t *page_table, const int32_t *ctx_lens, void *out, void *hip_stream);
+size_t rollattn_static_scratch_bytes(void);
+int rollattn_static_init(void);
 
 /* Observation-append step: trajectory b contributes n_b = q_lens[b] query rows (its new
  * chunk, packed consecutively in q_chunk in batch order) that attend causally inside the

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "librollattn.so")
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
 EXPORTS = (
-    "attn_decode", "attn_append", "attn_decode_lse", "attn_append_lse", "attn_merge", "attn_step", "attn_decode_shared",
+    "attn_decode", "attn_decode_static", "rollattn_static_scratch_bytes", "rollattn_static_init", "attn_append", "attn_decode_lse", "attn_append_lse", "attn_merge", "attn_step", "attn_decode_shared",
     "kv_write", "rollattn_workspace_bytes",
     "rollattn_step_workspace_bytes", "rollattn_shared_workspace_bytes", "rollattn_debug_gather",
     "rollattn_debug_check_inputs",
@@ -63,6 +63,12 @@ def lib() -> ctypes.CDLL:
         dp = ctypes.POINTER(Desc)
         l.attn_decode.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         l.attn_decode.restype = ctypes.c_int
+        l.attn_decode_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+        l.attn_decode_static.restype = ctypes.c_int
+        l.rollattn_static_scratch_bytes.argtypes = []
+        l.rollattn_static_scratch_bytes.restype = ctypes.c_size_t
+        l.rollattn_static_init.argtypes = []
+        l.rollattn_static_init.restype = ctypes.c_int
         l.attn_append.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         l.attn_append.restype = ctypes.c_int
         l.attn_decode_lse.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -171,6 +177,19 @@ def attn_decode(q, k_pages, v_pages, page_table, ctx_lens, *, sm_scale, k_scale=
                            _ptr(ctx_lens), _ptr(out), _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise RollattnError(rc, "attn_decode")
+    return out
+
+
+def attn_decode_static(q, k_pages, v_pages, page_table, ctx_lens, *, sm_scale, k_scale=None, v_scale=None,
+                       out, stream=None) -> torch.Tensor:
+    """attn_decode without a workspace: the library's built-in scratch array takes its place.  `out` is the
+    caller's (this call allocates nothing)."""
+    _check_contig(q, k_pages, v_pages, page_table, ctx_lens, k_scale, v_scale, out)
+    desc = make_desc(q, k_pages, page_table, sm_scale=sm_scale, k_scale=k_scale, v_scale=v_scale)
+    rc = lib().attn_decode_static(ctypes.byref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(page_table),
+                                  _ptr(ctx_lens), _ptr(out), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "attn_decode_static")
     return out
 
 

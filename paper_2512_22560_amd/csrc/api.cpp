@@ -10,6 +10,12 @@
 
 #include "rollattn_internal.h"
 
+// Scratch memory of attn_decode_static, the decode call for callers that cannot allocate: one array per GPU,
+// part of the library's code object, alive until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address it stands for is looked up once per device (static_scratch_ptr).
+constexpr size_t kStaticScratchBytes = (size_t)36 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace rollattn {
 
 namespace {
@@ -295,6 +301,53 @@ int attn_decode(const rollattn_desc* desc, const void* q, const void* k_pages, c
                 const int32_t* page_table, const int32_t* ctx_lens, void* out, void* workspace,
                 size_t workspace_bytes, void* hip_stream) {
   return decode_impl(desc, q, k_pages, v_pages, page_table, ctx_lens, out, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_static_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU, null until looked up
+
+// Address of the current device's copy of `scratch`; the lookup runs once per device, with that device current.
+int static_scratch_ptr(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e);
+  if (dev < 0 || dev >= kMaxDevices) return fail_hip(hipErrorInvalidDevice);
+  {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_static_ptr[dev]) {
+      *out = g_static_ptr[dev];
+      return ROLLATTN_OK;
+    }
+  }
+  void* p = nullptr;
+  e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return fail_hip(e);
+  if (!p) return fail_hip(hipErrorInvalidSymbol);
+  std::lock_guard<std::mutex> lk(g_mu);
+  g_static_ptr[dev] = p;
+  *out = p;
+  return ROLLATTN_OK;
+}
+}  // namespace
+
+size_t rollattn_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int rollattn_static_init(void) {
+  void* p = nullptr;
+  return static_scratch_ptr(&p);
+}
+
+int attn_decode_static(const rollattn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                       const int32_t* page_table, const int32_t* ctx_lens, void* out, void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (desc->batch == 0) return ROLLATTN_OK;
+  if (decode_layout(*desc).total > kStaticScratchBytes) return ROLLATTN_ELIMIT;
+  void* ws = nullptr;
+  rc = static_scratch_ptr(&ws);
+  if (rc) return rc;
+  return decode_impl(desc, q, k_pages, v_pages, page_table, ctx_lens, out, ws, kStaticScratchBytes, hip_stream, nullptr);
 }
 
 // attn_append proper.  table_stride: int32 entries between the page-table rows of consecutive
@@ -609,6 +662,7 @@ const char* rollattn_status_string(int status) {
     case ROLLATTN_EALIGN: return "device pointer not 16-byte aligned";
     case ROLLATTN_EWORKSPACE: return "workspace smaller than rollattn_workspace_bytes()";
     case ROLLATTN_EHIP: return "HIP call failed (see rollattn_last_hip_error)";
+    case ROLLATTN_ELIMIT: return "the call needs more scratch memory than the library's built-in array holds (rollattn_static_scratch_bytes)";
     default: return "unknown status";
   }
 }
@@ -620,6 +674,6 @@ const char* rollattn_last_hip_error(void) {
   return copy.c_str();
 }
 
-int rollattn_version(void) { return 100; }
+int rollattn_version(void) { return 101; }
 
 }  // extern "C"

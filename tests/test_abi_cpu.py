@@ -52,6 +52,11 @@ def test_descriptor_errors_are_reported_before_any_launch():
     assert lib.attn_append(ctypes.byref(_desc()), fake, fake, fake, 0, 0, fake, fake, fake, fake, fake, fake, 0, None) == 0
     assert lib.attn_append(ctypes.byref(_desc()), fake, fake, fake, -1, 0, fake, fake, fake, fake, fake, fake, 0, None) == -1
     assert lib.attn_append(ctypes.byref(_desc()), fake, fake, fake, 8, 2, fake, fake, fake, fake, fake, fake, 16, None) == -5
+    # the workspace-free decode call checks its descriptor, then its size limit, before it touches the device
+    assert lib.attn_decode_static(ctypes.byref(_desc(head_dim=96)), fake, fake, fake, fake, fake, fake, None) == -2
+    assert lib.attn_decode_static(ctypes.byref(_desc(batch=0)), fake, fake, fake, fake, fake, fake, None) == 0
+    assert lib.attn_decode_static(ctypes.byref(_desc(batch=12_000_000)), fake, fake, fake, fake, fake, fake, None) == -7
+    assert lib.rollattn_static_scratch_bytes() == 36 << 20
     def write(d, total_q=4, k_new=fake, ks=fake, max_q=1):
         return lib.kv_write(ctypes.byref(d), k_new, fake, fake, fake, total_q, max_q, fake, fake, fake, fake, ks, fake, None)
     assert write(_desc(), total_q=0) == 0                          # nothing to write: success, no launch

@@ -5,9 +5,9 @@
 // head of the group) pair, token-major, so the G heads that share the KV head reuse every K/V
 // tile.  Eight waves of 32 rows each walk the visible KV range in 64-token blocks (four pages)
 // that the workgroup stages once in LDS, always as bf16: bf16 pools are copied from HBM into LDS
-// directly (no register stop, ring of three tiles per pool), FP8 pools pass through registers to
-// be widened (two tiles per pool, loads two blocks ahead); page scales are applied in float to S
-// (K scale) and to P (V scale).  Per block a wave computes
+// directly (no register stop, ring of four tiles per pool), FP8 pools pass through registers to
+// be widened (two tiles per pool, loads two blocks ahead of the LDS write).  Per block a wave
+// computes
 //   S^T = K Q^T        tokens x rows, v_mfma_f32_32x32x16_bf16, K rows as A operand
 //   O^T += V^T P^T     dims x rows, V read transposed with ds_read_b64_tr_b16
 // The transposed products keep "row" on the lane axis in both accumulators: the softmax
@@ -19,11 +19,24 @@
 // take turns.  Here every block is cut into a matrix phase (the second product of the previous
 // block, then the first product of this one) and a vector phase (this block's softmax), each
 // closed by a workgroup barrier, and waves 4-7 enter the sequence one barrier late: on every SIMD
-// one wave feeds the matrix core while the other does the exponentials.  A wave in a phase has
-// no partner to hide its latencies, so the matrix phase reads its LDS operands several steps
-// ahead in a fixed source-order schedule, and it also carries all the staging work (addresses,
-// loads, FP8 widening), threaded between the MFMAs, because the vector phase is the one bound by
-// its own instruction stream.
+// one wave feeds the matrix core while the other does the exponentials.  A wave in its matrix
+// phase has no partner to hide its latencies, so it reads its LDS operands several steps ahead in
+// a fixed source-order schedule and issues as little else as possible: measured with per-phase
+// cycle counters, a vector-memory instruction issued between the MFMAs costs the phase 70-90
+// cycles (four of them stretched 32 MFMAs from 1270 to 1400 cycles), while the same instruction
+// costs the vector phase little more than its issue slot.  All tile loads and the scalar loads of
+// page ids and page scales therefore belong to the vector phase; only the widening of FP8 tiles
+// (conversions and LDS writes of registers loaded two blocks earlier) stays between the MFMAs,
+// where it was measured to cost less than in a vector phase that is bound by its own instruction
+// stream.  The vector phase keeps its VALU work short in turn:
+//   bf16 pools: the query is multiplied by sm_scale * log2(e) once, when it is loaded (one extra
+//     bf16 rounding of q, far below the rounding of P), and the score accumulators start from
+//     minus the row's reference instead of zero, so the MFMA result already is the exponent and
+//     the softmax is one v_exp_f32 per element with nothing in front of it;
+//   FP8 pools: the score needs its page's K scale anyway (one fused multiply-add per element,
+//     whose addend carries minus the reference), and the V scale of the page is folded into that
+//     addend as log2(vs), so P comes out of the exponential already weighted for the second
+//     product; the row sum divides each page's share by vs again (four multiplies per block).
 #include <type_traits>
 #include <utility>
 
@@ -96,9 +109,10 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   constexpr int kDT = D / 32;                      // 32-wide output tiles along D
   static_assert((kBlockTokens * kSrcChunks) % kThreads == 0 || kBlockTokens * kSrcChunks < kThreads, "staging shape");
 
-  // bf16 pools go from HBM straight into LDS (no register stop), which needs a ring of three tiles
-  // per pool to give the loads time; FP8 pools pass through registers to be widened, two tiles.
-  constexpr int kRing = FP8 ? 2 : 3;
+  // bf16 pools go from HBM straight into LDS (no register stop): a ring of four tiles per pool gives
+  // every load a whole block period to land.  FP8 pools pass through registers to be widened: their
+  // LDS writes are immediate, two tiles are enough.
+  constexpr int kRing = FP8 ? 2 : 4;
   __shared__ __attribute__((aligned(1024))) unsigned char k_lds[kRing][kTileBytes];
   __shared__ __attribute__((aligned(1024))) unsigned char v_lds[kRing][kTileBytes];
 
@@ -165,6 +179,10 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     for (int kk = 0; kk < kKK; ++kk) {
       bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
       if (row_ok) v = *(const bf16x8*)(qrow + kk * 16 + h2 * 8);
+      if constexpr (!FP8) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (__bf16)((float)v[e] * a.scale_log2);
+      }
       qop[kk] = v;
     }
   }
@@ -175,12 +193,16 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  floatx16 negm;            // bf16 pools: minus the row's reference in every element, the value the score accumulators start from
+#pragma unroll
+  for (int i = 0; i < 16; ++i) negm[i] = 0.f;
   const bool positive_scale = a.scale_log2 > 0.f;   // the usual case; FP8 page scales are positive too
 
   // ---- staging.  Unit u = (K block u + 1, V block u): the two tiles that the matrix phase of
   // block u + 1 reads; block j lives in ring slot j % kRing of its pool.  Per thread and load, the
   // byte offset inside a (page, head) tile never changes: only the page does, and that is a scalar.
-  // Branch-free on purpose (loads can then be waited on by count).  Rows at or past L_b (ragged
+  // Every wave stages its share of a unit in its vector phase; branch-free on purpose (loads can
+  // then be waited on by count).  Rows at or past L_b (ragged
   // last block, or a block index clamped at the end of the loop) re-read the trajectory's last
   // token instead: finite data that the causal / length mask never lets through.
   const int live_pages = (ctx + kPageSize - 1) / kPageSize;
@@ -267,22 +289,25 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 
   // FP8: scales of the four pages of a block (scalar loads), folded with the softmax scale; the page
   // ids behind them are fetched one vector phase before the scales, the scales one vector phase before use
-  float ksc_cur[4], vsc_cur[4];
+  float ksc_cur[4], lvs_cur[4], ivs_cur[4];   // per page of the block: K scale times softmax scale, log2 of the V scale, its reciprocal
   int spid[kPagesPerBlock];
   auto fetch_spids = [&](int blk) __attribute__((always_inline)) {
 #pragma unroll
     for (int p = 0; p < kPagesPerBlock; ++p)
       spid[p] = FP8 ? table[min(min(blk, last_blk) * kPagesPerBlock + p, live_pages - 1)] : 0;
   };
-  auto load_scales = [&](float* ks, float* vs) __attribute__((always_inline)) {
+  auto load_scales = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int p = 0; p < kPagesPerBlock; ++p) {
       if (FP8) {
-        ks[p] = k_scale_c[spid[p]] * a.scale_log2;
-        vs[p] = v_scale_c[spid[p]];
+        const float vs = v_scale_c[spid[p]];
+        ksc_cur[p] = k_scale_c[spid[p]] * a.scale_log2;
+        lvs_cur[p] = __builtin_amdgcn_logf(vs);
+        ivs_cur[p] = __builtin_amdgcn_rcpf(vs);
       } else {
-        ks[p] = a.scale_log2;
-        vs[p] = 1.f;
+        ksc_cur[p] = 1.f;
+        lvs_cur[p] = 0.f;
+        ivs_cur[p] = 1.f;
       }
     }
   };
@@ -310,9 +335,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   // ---- matrix phase: up to 32 MFMA steps, O^T += V^T P^T for the previous block (steps 0-15, V buffer
   // at vbo) and S^T = K Q^T for this one (steps 16-31, K buffer at kbo).  Every step needs one 32x16 operand
   // from LDS; the reads run kAhead steps in front of the MFMAs that consume them, because during
-  // this phase no second wave hides the LDS latency.  After step t the caller's piece(p0, p1) runs
-  // with [p0, p1) the slice of 32 schedule positions that the step covers: that is where the
-  // staging work of the phase is threaded between the MFMAs.
+  // this phase no second wave hides the LDS latency.  After the step at schedule position pos the
+  // caller's piece(pos) runs: the FP8 path threads its LDS writes between the MFMAs there.
   constexpr int kAhead = 4;
   auto matrix_phase = [&](auto first_c, auto last_c, int kbo, int vbo, auto&& piece) __attribute__((always_inline)) {
     constexpr int T0 = decltype(first_c)::value, T1 = decltype(last_c)::value;
@@ -347,10 +371,16 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         constexpr int u = t - 16, kk = u >> 1, sub = u & 1;
         if constexpr (kk < kKK) {
           if constexpr (kk == 0) {
+            if constexpr (FP8) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
+              for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
+              s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ops[t], qop[kk], s[sub], 0, 0, 0);
+            } else {
+              s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ops[t], qop[kk], negm, 0, 0, 0);
+            }
+          } else {
+            s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ops[t], qop[kk], s[sub], 0, 0, 0);
           }
-          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ops[t], qop[kk], s[sub], 0, 0, 0);
         }
       }
     };
@@ -364,27 +394,38 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
       if constexpr (t >= T0 && t < T1) {
         if constexpr (t + kAhead < T1) fetch(std::integral_constant<int, t + kAhead>{});
         fire(t_c);
-        piece(std::integral_constant<int, (t - T0) * 32 / (T1 - T0)>{}, std::integral_constant<int, (t + 1 - T0) * 32 / (T1 - T0)>{});
+        piece(std::integral_constant<int, (t - T0) * 32 / (T1 - T0)>{});
         __builtin_amdgcn_sched_barrier(0);           // the source order of the steps is the schedule
       }
     });
   };
   constexpr std::integral_constant<int, 0> c0{};
   // ---- vector phase: online softmax of block blk.  Register i of s[sub] is token
-  // blk*64 + sub*32 + (i/8)*16 + h2*8 + (i%8) of row n32.  Scores stay unscaled in s; the scale (and,
-  // for FP8, the K scale of the token's page) is folded into the exponent with one fused
-  // multiply-add per element: p = 2^(s * sc - m).
+  // blk*64 + sub*32 + (i/8)*16 + h2*8 + (i%8) of row n32.
+  //   bf16 pools: s already is the exponent (scaled query, accumulators started from minus the reference).
+  //   FP8 pools:  s is the raw product with the codes; per page sc = K scale times the softmax scale and
+  //               ad = log2(V scale) - reference, so p' = 2^(s * sc + ad) = p * vs is the weight the second
+  //               product needs, and the row sum takes each page's share divided by vs again.
+  // The reference m_run of a row only moves when it has to.  The exponentials are taken against the
+  // reference as it stands, without looking for the block's maximum first, and may exceed one: float
+  // sums and bf16 P hold large values with the same relative precision as small ones.  Only when the p
+  // of one lane add up to more than kSumLimit (so that no single p ever exceeds it), or when a row has no
+  // reference yet, does the wave find the true maxima, move the references there, rescale the
+  // accumulators and redo the block's exponentials.  In all other blocks the maximum, a chain of
+  // dependent steps across the row, is never computed.
   auto softmax = [&](int blk) __attribute__((always_inline)) {
     float sc[4];
+    if constexpr (FP8) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) sc[p] = ksc_cur[p];
-    if (!positive_scale) {                             // rare: scale the scores themselves instead
+      for (int p = 0; p < 4; ++p) sc[p] = ksc_cur[p];
+      if (!positive_scale) {                           // rare: scale the scores themselves instead
 #pragma unroll
-      for (int sub = 0; sub < kSubs; ++sub)
+        for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[sub][i] *= sc[sub * 2 + (i >> 3)];
+          for (int i = 0; i < 16; ++i) s[sub][i] *= sc[sub * 2 + (i >> 3)];
 #pragma unroll
-      for (int p = 0; p < 4; ++p) sc[p] = 1.f;
+        for (int p = 0; p < 4; ++p) sc[p] = 1.f;
+      }
     }
     const int tok0 = blk * kBlockTokens;
     if (tok0 + kBlockTokens - 1 > wave_min_pos) {      // causal edge or ragged end inside this block
@@ -396,55 +437,49 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
           if (tok > my_pos) s[sub][i] = -INFINITY;
         }
     }
-    // The reference m_run of a row only moves when it has to.  The exponentials are taken against the
-    // reference as it stands, p = 2^(s * sc - m_run), without looking for the block's maximum first, and may
-    // exceed one: float sums and bf16 P hold large values with the same relative precision as small
-    // ones.  Only when the p of one lane add up to more than kSumLimit (so that no single p ever exceeds
-    // it), or when a row has no reference yet, does the wave find the true maxima, move the references
-    // there, rescale the accumulators and redo the block's exponentials.  In all other blocks the maximum, a chain of dependent steps across the row, is never
-    // computed.
-    const float m_old = (m_run == -INFINITY) ? 0.f : m_run;
+    const float m_old = (m_run == -INFINITY) ? 0.f : m_run;   // what the exponents in s (bf16 pools) are relative to
     float p[kSubs][16];
+    // exponentials of the block against reference m_old + shift, and this lane's share of the row sums
+    auto exponentials = [&](auto first_c, float shift) __attribute__((always_inline)) -> float {
+      float ad[4], psum[4];
+      if constexpr (FP8) {
 #pragma unroll
-    for (int sub = 0; sub < kSubs; ++sub)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) p[sub][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[sub * 2 + (i >> 3)], -m_old));
-    float psum[4];
-#pragma unroll
-    for (int sub = 0; sub < kSubs; ++sub)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if ((i & 7) == 0) psum[sub * 2 + (i >> 3)] = p[sub][i];
-        else psum[sub * 2 + (i >> 3)] += p[sub][i];
+        for (int pg = 0; pg < 4; ++pg) ad[pg] = lvs_cur[pg] - (m_old + shift);
       }
-    float lane_sum = (psum[0] + psum[1]) + (psum[2] + psum[3]);
+#pragma unroll
+      for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int pg = sub * 2 + (i >> 3);
+          float x;
+          if constexpr (FP8) x = __builtin_fmaf(s[sub][i], sc[pg], ad[pg]);
+          else if constexpr (decltype(first_c)::value) x = s[sub][i];
+          else x = s[sub][i] - shift;
+          p[sub][i] = __builtin_amdgcn_exp2f(x);
+          if ((i & 7) == 0) psum[pg] = p[sub][i];
+          else psum[pg] += p[sub][i];
+        }
+      if constexpr (FP8) return (psum[0] * ivs_cur[0] + psum[1] * ivs_cur[1]) + (psum[2] * ivs_cur[2] + psum[3] * ivs_cur[3]);
+      else return (psum[0] + psum[1]) + (psum[2] + psum[3]);
+    };
+    float lane_sum = exponentials(std::true_type{}, 0.f);
     // (an infinite or undefined sum also fails the comparison and takes the slow path)
     const bool bump = row_ok && (m_run == -INFINITY || !(lane_sum <= kSumLimit));
     if (__builtin_amdgcn_ballot_w64(bump)) {
-      // sc > 0 here, so the row maximum can be taken on the unscaled scores (of each page, where the
-      // pages have scales of their own)
-      float mloc;
-      if (FP8) {
-        float pm[4];
+      // largest exponent of the block: FP8 page scales and the softmax scale are positive here, so the maximum
+      // can be taken on the raw products of each page
+      float pm[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int sub = q >> 1, o = (q & 1) * 8;
-          float x = fmaxf(fmaxf(s[sub][o], s[sub][o + 1]), s[sub][o + 2]);
-          x = fmaxf(fmaxf(x, s[sub][o + 3]), s[sub][o + 4]);
-          x = fmaxf(fmaxf(x, s[sub][o + 5]), s[sub][o + 6]);
-          pm[q] = fmaxf(x, s[sub][o + 7]);
-        }
-        mloc = fmaxf(fmaxf(pm[0] * sc[0], pm[1] * sc[1]), fmaxf(pm[2] * sc[2], pm[3] * sc[3]));
-      } else {
-        float x[kSubs];
-#pragma unroll
-        for (int sub = 0; sub < kSubs; ++sub) {
-          x[sub] = fmaxf(fmaxf(s[sub][0], s[sub][1]), s[sub][2]);
-#pragma unroll
-          for (int i = 3; i < 15; i += 2) x[sub] = fmaxf(fmaxf(x[sub], s[sub][i]), s[sub][i + 1]);
-        }
-        mloc = fmaxf(fmaxf(x[0], s[0][15]), fmaxf(x[1], s[1][15])) * sc[0];
+      for (int q = 0; q < 4; ++q) {
+        const int sub = q >> 1, o = (q & 1) * 8;
+        float x = fmaxf(fmaxf(s[sub][o], s[sub][o + 1]), s[sub][o + 2]);
+        x = fmaxf(fmaxf(x, s[sub][o + 3]), s[sub][o + 4]);
+        x = fmaxf(fmaxf(x, s[sub][o + 5]), s[sub][o + 6]);
+        pm[q] = fmaxf(x, s[sub][o + 7]);
       }
+      float mloc;
+      if constexpr (FP8) mloc = fmaxf(fmaxf(pm[0] * sc[0], pm[1] * sc[1]), fmaxf(pm[2] * sc[2], pm[3] * sc[3]));
+      else mloc = fmaxf(fmaxf(pm[0], pm[1]), fmaxf(pm[2], pm[3])) + m_old;
       const float m_new = fmaxf(m_run, xor32_max(mloc));           // the same in both lanes of a row
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;     // rows that see nothing yet
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
@@ -454,24 +489,17 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[dt][i] *= alpha;
       m_run = m_new;
+      if constexpr (!FP8) {
 #pragma unroll
-      for (int sub = 0; sub < kSubs; ++sub)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          p[sub][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][i], sc[sub * 2 + (i >> 3)], -m_safe));
-          if ((i & 7) == 0) psum[sub * 2 + (i >> 3)] = p[sub][i];
-          else psum[sub * 2 + (i >> 3)] += p[sub][i];
-        }
-      lane_sum = (psum[0] + psum[1]) + (psum[2] + psum[3]);
+        for (int i = 0; i < 16; ++i) negm[i] = -m_safe;
+      }
+      lane_sum = exponentials(std::false_type{}, m_safe - m_old);
     }
     l_run += lane_sum;
 #pragma unroll
     for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int p4 = sub * 2 + (i >> 3);
-        pop[sub][i >> 3][i & 7] = (__bf16)(FP8 ? p[sub][i] * vsc_cur[p4] : p[sub][i]);
-      }
+      for (int i = 0; i < 16; ++i) pop[sub][i >> 3][i & 7] = (__bf16)p[sub][i];
     // the probabilities are finished here, in this phase, not wherever the compiler would like to sink them
 #pragma unroll
     for (int sub = 0; sub < kSubs; ++sub)
@@ -484,34 +512,38 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   };
 
   // Two phases per block, a matrix phase (O += V P of the previous block, then S = K Q^T of this
-  // one, with the workgroup's staging traffic threaded in) and a vector phase (softmax of this block), each
-  // closed by a workgroup barrier.  The trailing half of the waves entered the sequence one barrier
-  // late, so on every SIMD one wave is in its matrix phase while the other is in its vector phase
-  // and the two pipelines run side by side instead of taking turns.  K block i and V block i - 1 are
-  // read in phases 2i and 2i + 1 (leading, trailing half).
-  //   FP8:  unit i is written to LDS during those same two phases, into the other buffers, from
-  //         registers loaded two blocks earlier.
-  //   bf16: unit i is in flight from HBM from the matrix phase of block i - 1 on and must have
-  //         landed when phase 2i + 2 starts; every wave waits for its own loads at the end of its
-  //         matrix phase of block i.
-  // FP8: LDS writes must be complete, so the usual fence + barrier.  bf16: a bare barrier; the loads
-  // in flight must stay in flight across it, and a fence would wait for them.
-#define BARRIER_RAW() do { if (FP8) __syncthreads(); else asm volatile("s_barrier" ::: "memory"); } while (0)
+  // one: MFMAs and their LDS operand reads, nothing else) and a vector phase (softmax of this block and
+  // the wave's share of the staging), each closed by a workgroup barrier.  The trailing half of the
+  // waves entered the sequence one barrier late, so on every SIMD one wave is in its matrix phase
+  // while the other is in its vector phase and the two pipelines run side by side instead of taking
+  // turns.  Phases are numbered by barriers: the leading half has its matrix phase of block i in phase
+  // 2i and its vector phase in 2i + 1, the trailing half in 2i + 1 and 2i + 2.  K block i and V block
+  // i - 1 are read in phases 2i and 2i + 1 and their ring slots are free from phase 2i + 2 on.
+  //   bf16: in its vector phase of block i a wave starts the loads of unit i + 2 (K block i + 3 into
+  //         the slot K block i - 1 left in phase 2i - 1 at the latest, V block i + 2 into the slot of
+  //         V block i - 2) and then waits until all but those newest loads have landed: unit i + 1,
+  //         a whole block period after it was started, and two barriers before phase 2i + 4 reads it.
+  //   FP8:  in its matrix phase of block i (phase 2i or 2i + 1) a wave widens its share of unit i
+  //         (K block i + 1, V block i; first read in phase 2i + 2) from registers into the tiles that
+  //         are not being read, and in the vector phase that follows it reloads those registers
+  //         with unit i + 2.
+  // FP8: the wave's LDS writes must be complete before the barrier, but its tile loads for later units
+  // must stay in flight across it (a full fence would wait for them too).  bf16: a bare barrier; the
+  // direct loads are awaited by count where they are issued.
+#define BARRIER_RAW() do { if (FP8) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); else asm volatile("s_barrier" ::: "memory"); } while (0)
 #define PHASE_END() do { __builtin_amdgcn_sched_barrier(0); BARRIER_RAW(); __builtin_amdgcn_sched_barrier(0); } while (0)
   constexpr std::integral_constant<int, 0> even{};
   constexpr std::integral_constant<int, 1> odd{};
   constexpr std::integral_constant<int, 16> c16{};
   constexpr std::integral_constant<int, 32> c32{};
-  // The tile loads and LDS writes are done by the wave that is in its matrix phase: that wave issues
-  // few instructions (32 MFMAs, 48 LDS reads), while the vector phase is bound by instruction issue.
-  // Page ids run ahead of the tile loads, so that no load ever waits for an address: U being the unit
-  // a wave issues in its next matrix phase (U = block + 2 through registers, block + 1 direct), toff
-  // holds its tile offsets for K block U and V block U - 1 and pid_new its page ids of K block U + 1.
-  constexpr int kLead = FP8 ? 2 : kRing - 2;
-  size_t toff[2][kLoads];      // rotated at the start of the matrix phase: then [0] is K block U + 1, [1] V block U
+  // Page ids run ahead of the tile loads, so that no load ever waits for an address: U = i + kLead being
+  // the unit whose loads a wave starts in its vector phase of block i, toff holds (on entry to that
+  // phase) the tile offsets of block U and pid_new the page ids of block U + 1.
+  constexpr int kLead = 2;
+  size_t toff[2][kLoads];      // rotated at the start of the staging step: then [0] is K block U + 1, [1] V block U
   int pid_new[kLoads];         // not yet turned into an offset
-  // ko[d]: byte offset of the ring slot of block i + d (i = the block whose matrix phase comes
-  // next); block i - 1 shares the slot of block i + kRing - 1.
+  // ko[d]: byte offset of the ring slot of block i + d (i = the block whose matrix phase came
+  // last); block i - 1 shares the slot of block i + kRing - 1.
   int ko[kRing];
 #pragma unroll
   for (int d = 0; d < kRing; ++d) ko[d] = d * kTileBytes;
@@ -520,9 +552,10 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     int h0[kLoads], h1[kLoads], h2[kLoads], h3[kLoads];
     fetch_pids(0, h0); fetch_pids(1, h1); fetch_pids(2, h2); fetch_pids(3, h3);
     fetch_spids(0);
-    load_scales(ksc_cur, vsc_cur);
+    load_scales();
     fetch_spids(1);
     if constexpr (FP8) {
+      // K block 0 goes to LDS here; units 0 and 1 wait in registers
       uintx4 k0[kLoads];
 #pragma unroll
       for (int j = 0; j < kLoads; ++j)
@@ -550,52 +583,60 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
       DMA_WAIT(kLead * 2 * kLoads);                  // K block 0 has landed
     }
     PHASE_END();
-    if (grp == 1) PHASE_END();                       // the trailing half starts one phase late
+    if (grp == 1) {                                  // the trailing half starts one phase late
+      // ... and the leading half reads unit 0 in phase 2, before the trailing half's first vector phase ends
+      if constexpr (!FP8) DMA_WAIT((kLead - 1) * 2 * kLoads);
+      PHASE_END();
+    }
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
-      pid_new[j] = kLead == 2 ? h3[j] : h2[j];
-      toff[0][j] = tile_off_of(kLead == 2 ? h2[j] : h1[j]);
+      pid_new[j] = h3[j];
+      toff[0][j] = tile_off_of(h2[j]);
     }
   }
-  // Staging share of the matrix phase of block i, cut into pieces; piece `pos` runs when the
-  // phase's schedule position passes pos.
-  auto stage = [&](int i, auto slot_c, auto p0_c, auto p1_c) __attribute__((always_inline)) {
-    constexpr int p0 = decltype(p0_c)::value, p1 = decltype(p1_c)::value;
-    auto at = [&](int pos) constexpr { return p0 <= pos && pos < p1; };
-    const int u = i + kLead;                         // the unit issued in this phase
-    if constexpr (at(0)) {
+  // Staging.  The tile addresses of the unit whose loads start in this vector phase:
+  auto stage_addresses = [&]() __attribute__((always_inline)) {
 #pragma unroll
-      for (int j = 0; j < kLoads; ++j) { toff[1][j] = toff[0][j]; toff[0][j] = tile_off_of(pid_new[j]); }
-    }
+    for (int j = 0; j < kLoads; ++j) { toff[1][j] = toff[0][j]; toff[0][j] = tile_off_of(pid_new[j]); }
+  };
+  // ... those loads, in the vector phase of block i (slot: the register slot that the matrix phase of block
+  // i has just drained, FP8 only) ...
+  auto stage_loads = [&](int i, auto slot_c) __attribute__((always_inline)) {
+    const int u = i + kLead;
     if constexpr (FP8) {
       constexpr int slot = decltype(slot_c)::value;
 #pragma unroll
       for (int j = 0; j < kLoads; ++j) {
-        const bool mine = kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens;
-        // unit i (K block i + 1, V block i) from registers to LDS, then the registers are reloaded
-        if (at(2 + 12 * j / kLoads) && mine) put(k_lds[0] + ko[1], woff[j][0], kreg[slot][j]);
-        if (at(6 + 12 * j / kLoads) && mine) put(v_lds[0] + ko[0], woff[j][1], vreg[slot][j]);
-        if (at(14 + 8 * j / kLoads) && mine) {
-          const TileAddr ka = tile_addr(a.k_pages, 0, u + 1, toff[0][j], j);
+        if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
+          const TileAddr ka = tile_addr(a.k_pages, 0, u + 1, toff[0][j], j), va = tile_addr(a.v_pages, 1, u, toff[1][j], j);
           kreg[slot][j] = *(const uintx4*)(ka.base + ka.off);
-        }
-        if (at(18 + 8 * j / kLoads) && mine) {
-          const TileAddr va = tile_addr(a.v_pages, 1, u, toff[1][j], j);
           vreg[slot][j] = *(const uintx4*)(va.base + va.off);
         }
       }
     } else {
 #pragma unroll
       for (int j = 0; j < kLoads; ++j) {
-        if (at(2 + 8 * j / kLoads)) dma(tile_addr(a.k_pages, 0, u + 1, toff[0][j], j), k_lds[0] + ko[kRing - 1] + wave * 1024 + j * kThreads * 16);
-        if (at(10 + 8 * j / kLoads)) dma(tile_addr(a.v_pages, 1, u, toff[1][j], j), v_lds[0] + ko[kRing - 2] + wave * 1024 + j * kThreads * 16);
+        dma(tile_addr(a.k_pages, 0, u + 1, toff[0][j], j), k_lds[0] + ko[kRing - 1] + wave * 1024 + j * kThreads * 16);
+        dma(tile_addr(a.v_pages, 1, u, toff[1][j], j), v_lds[0] + ko[kRing - 2] + wave * 1024 + j * kThreads * 16);
       }
-      if constexpr (at(26)) DMA_WAIT(kLead * 2 * kLoads);   // everything but the kLead newest units has landed
+      DMA_WAIT(2 * kLoads);                          // everything but the unit just started has landed
     }
   };
-  // Scalar loads (page ids of the unit issued two matrix phases from now, FP8 page scales of the next
-  // block) go out at the start of the vector phase and are awaited at its end: that phase has no LDS
-  // traffic whose waits an outstanding scalar load would turn into full drains.
+  // ... and, FP8 only, the widening of unit i (K block i + 1, V block i) from registers into LDS during the
+  // matrix phase of block i, at two fixed places between its MFMAs.
+  auto stage_widen = [&](auto slot_c, auto pos_c) __attribute__((always_inline)) {
+    if constexpr (FP8) {
+      constexpr int slot = decltype(slot_c)::value, pos = decltype(pos_c)::value;
+#pragma unroll
+      for (int j = 0; j < kLoads; ++j) {
+        const bool mine = kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens;
+        if (pos == 2 + 12 * j / kLoads && mine) put(k_lds[0] + ko[1], woff[j][0], kreg[slot][j]);
+        if (pos == 6 + 12 * j / kLoads && mine) put(v_lds[0] + ko[0], woff[j][1], vreg[slot][j]);
+      }
+    }
+  };
+  // Scalar loads (page ids of the unit started two vector phases from now, FP8 page scales of the next
+  // block) go out before the softmax and are awaited after it.
   auto scalar_issue = [&](int i) __attribute__((always_inline)) {
     fetch_pids(i + kLead + 2, pid_new);
     if constexpr (FP8) {
@@ -621,11 +662,11 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         spid[p] = __builtin_amdgcn_readfirstlane(spid[p]);
         asm volatile("" : "+s"(spid[p]));
         ksc_cur[p] = __uint_as_float(kraw[p]) * a.scale_log2;   // the softmax of this block is done with the old ones
-        vsc_cur[p] = __uint_as_float(vraw[p]);
+        lvs_cur[p] = __builtin_amdgcn_logf(__uint_as_float(vraw[p]));
+        ivs_cur[p] = __builtin_amdgcn_rcpf(__uint_as_float(vraw[p]));
       }
     }
   };
-  auto no_piece = [](auto, auto) {};
   auto next_block = [&]() __attribute__((always_inline)) {
     const int t = ko[0];
 #pragma unroll
@@ -635,61 +676,42 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   // A wave whose 32 rows all lie past the tile's last row (ragged last tile of a chunk, or a group
   // call with few rows) keeps its share of the staging and every barrier but skips the products and
   // the softmax: it would only compete with the wave it shares a SIMD with.
-  auto idle_phase = [&](auto&& piece) __attribute__((always_inline)) {
-    static_for<32>([&](auto t_c) __attribute__((always_inline)) {
-      constexpr int t = decltype(t_c)::value;
-      piece(std::integral_constant<int, t>{}, std::integral_constant<int, t + 1>{});
-    });
-  };
   auto run = [&](auto active_c) __attribute__((always_inline)) {
     constexpr bool kActive = decltype(active_c)::value;
-    // block 0 has no predecessor: scores only
-    if constexpr (kActive) {
-      __builtin_amdgcn_s_setprio(1);
-      matrix_phase(c16, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(0, even, p0, p1); });
-      __builtin_amdgcn_s_setprio(0);
-    } else {
-      idle_phase([&](auto p0, auto p1) __attribute__((always_inline)) { stage(0, even, p0, p1); });
-    }
-    PHASE_END();
-    scalar_issue(0);
-    if constexpr (kActive) softmax(0);
-    scalar_await();
-    PHASE_END();
-    next_block();
-    for (int i = 1; i < n_blocks; i += 2) {
+    // slot: parity of the block, the register slot of the unit that is widened and reloaded (FP8)
+    auto matrix = [&](auto first_c, auto last_c, auto slot_c) __attribute__((always_inline)) {
+      auto piece = [&](auto pos_c) __attribute__((always_inline)) { stage_widen(slot_c, pos_c); };
       if constexpr (kActive) {
         __builtin_amdgcn_s_setprio(1);
-        matrix_phase(c0, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i, odd, p0, p1); });
+        matrix_phase(first_c, last_c, ko[0], ko[kRing - 1], piece);
         __builtin_amdgcn_s_setprio(0);
       } else {
-        idle_phase([&](auto p0, auto p1) __attribute__((always_inline)) { stage(i, odd, p0, p1); });
+        static_for<32>(piece);
       }
       PHASE_END();
+    };
+    auto vector = [&](int i, auto slot_c) __attribute__((always_inline)) {
+      stage_addresses();
+      stage_loads(i, slot_c);
       scalar_issue(i);
       if constexpr (kActive) softmax(i);
       scalar_await();
       PHASE_END();
       next_block();
+    };
+    matrix(c16, c32, even);                          // block 0 has no predecessor: scores only
+    vector(0, even);
+    for (int i = 1; i < n_blocks; i += 2) {
+      matrix(c0, c32, odd);
+      vector(i, odd);
       if (i + 1 < n_blocks) {
-        if constexpr (kActive) {
-          __builtin_amdgcn_s_setprio(1);
-          matrix_phase(c0, c32, ko[0], ko[kRing - 1], [&](auto p0, auto p1) __attribute__((always_inline)) { stage(i + 1, even, p0, p1); });
-          __builtin_amdgcn_s_setprio(0);
-        } else {
-          idle_phase([&](auto p0, auto p1) __attribute__((always_inline)) { stage(i + 1, even, p0, p1); });
-        }
-        PHASE_END();
-        scalar_issue(i + 1);
-        if constexpr (kActive) softmax(i + 1);
-        scalar_await();
-        PHASE_END();
-        next_block();
+        matrix(c0, c32, even);
+        vector(i + 1, even);
       }
     }
     if constexpr (kActive) {
       __builtin_amdgcn_s_setprio(1);
-      matrix_phase(c0, c16, 0, ko[kRing - 1], no_piece);
+      matrix_phase(c0, c16, 0, ko[kRing - 1], [](auto) {});
       __builtin_amdgcn_s_setprio(0);
     }
   };

@@ -17,6 +17,12 @@ from tests.helpers import oracle_args
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 LSE_TOL = {"f32": 1e-4, "bf16": 2e-3}      # absolute, in log2 units (values reach ~ 20)
+# The append kernel over bf16 pools multiplies the query by sm_scale * log2(e) and rounds it to bf16 once, when it loads
+# it: every product q_d k_d of a score then carries an independent relative error of at most 2^-9, which for unit-variance
+# inputs and D = 128 is about 1.6e-3 (rms) in log2 units per score.  The logarithm of the denominator moves by a weighted
+# mean of these, at most by the largest of them: a few standard deviations.  (The outputs themselves stay inside the bar
+# of the bf16 paths, which the same tests check.)
+LSE_TOL_APPEND_BF16_POOLS = 1e-2
 
 
 def _oracle_lse(b, q_lens):
@@ -25,13 +31,14 @@ def _oracle_lse(b, q_lens):
                       q_dtype=a["q_dtype"], kv_dtype=a["kv_dtype"], k_scale=a["k_scale"])
 
 
-def _check_lse(got, ref, qd, what):
+def _check_lse(got, ref, qd, what, tol=None):
+    tol = LSE_TOL[qd] if tol is None else tol
     g = got.double().cpu().numpy()
     assert g.shape == ref.shape
     empty = np.isneginf(ref)
     assert np.array_equal(np.isneginf(g), empty), f"{what}: rows without tokens"
     err = np.abs(g[~empty] - ref[~empty])
-    assert err.size == 0 or err.max() <= LSE_TOL[qd], f"{what}: lse max abs err {err.max():.3e}"
+    assert err.size == 0 or err.max() <= tol, f"{what}: lse max abs err {err.max():.3e}"
 
 
 @pytest.mark.parametrize("hq,hkv,d,qd,kvd", [(8, 2, 64, "f32", "f32"), (32, 8, 128, "bf16", "bf16"), (32, 2, 128, "bf16", "fp8_e4m3"),
@@ -60,7 +67,7 @@ def test_append_denominators(hq, hkv, d, qd, kvd):
     torch.cuda.synchronize()
     assert torch.equal(out, gpu_append(b))
     check(out, oracle_append(b), qd, "append with lse")
-    _check_lse(lse, _oracle_lse(b, b.q_lens_host), qd, "append")
+    _check_lse(lse, _oracle_lse(b, b.q_lens_host), qd, "append", tol=LSE_TOL_APPEND_BF16_POOLS if kvd == "bf16" else None)
 
 
 @pytest.mark.parametrize("qd,kvd,d", [("f32", "f32", 64), ("bf16", "bf16", 128), ("bf16", "fp8_e4m3", 128)])

@@ -403,7 +403,14 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
   if (e != hipSuccess) return fail_hip(e);
   {
     ProfileScope prof(s);
-    const int grid = (int)std::min<int64_t>((int64_t)w.workers * a.hkv, INT32_MAX);
+    // one workgroup per (tile, KV head); with fewer than 8 heads the kernel deals runs of tiles to the XCDs
+    // of a head, which needs up to one run of slack per XCD (see the kernel's index mapping)
+    int64_t grid64 = (int64_t)w.workers * a.hkv;
+    if (a.hkv < kXcds && kXcds % a.hkv == 0) {
+      const int64_t parts = kXcds / a.hkv;
+      grid64 = kXcds * (((int64_t)w.workers + parts - 1) / parts + kAppendXcdRun);
+    }
+    const int grid = (int)std::min<int64_t>(grid64, INT32_MAX);
     e = launch_append_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, grid, s);
     prof.stop();
   }

@@ -126,8 +126,23 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   const int hkv = a.hkv;
   const int tile_tokens = a.tile_tokens;
   const int n_tiles = a.header[kPlanTiles];
-  const int tile = blockIdx.x / hkv;
-  const int g = blockIdx.x - tile * hkv;
+  // Workgroup -> (tile, KV head).  Workgroups go to the 8 XCDs round-robin and every XCD has an L2 of its
+  // own; tiles of one trajectory and KV head walk the same K/V stream and should share one L2.  With the
+  // plain order (head fastest) that holds when the head count is a multiple of 8: XCD x then only ever sees
+  // heads x, x + 8, ...  With 1, 2 or 4 KV heads a head's tiles would be dealt to 8, 4 or 2 XCDs and each of
+  // them would fetch the whole stream; there the 8 / Hkv XCDs that serve a head take turns by runs of up to
+  // 32 consecutive tiles of the list (one per CU of an XCD; the list keeps a trajectory's tiles together).
+  int tile, g;
+  if (hkv < kXcds && kXcds % hkv == 0) {
+    const int x = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int parts = kXcds / hkv;
+    const int run = min(kAppendXcdRun, (n_tiles + parts - 1) / parts);
+    g = x % hkv;
+    tile = run > 0 ? (slot / run) * (parts * run) + (x / hkv) * run + slot % run : n_tiles;
+  } else {
+    tile = blockIdx.x / hkv;
+    g = blockIdx.x - tile * hkv;
+  }
   if (tile >= n_tiles) return;
   const int b = a.tile_b[tile];
   const int q0 = a.tile_q0[tile];

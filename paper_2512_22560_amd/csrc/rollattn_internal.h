@@ -17,6 +17,8 @@ constexpr int kMfmaHeadTile = 16;       // query heads per MFMA decode row
 constexpr int kF32DecodeWgs = 4 * kNumCUs;    // one workgroup-worker each
 constexpr int kF32HeadTile = 4;         // query heads per float32 decode row
 constexpr int kAppendTileRows = 256;    // query rows (token, head-in-group pairs) per append workgroup
+constexpr int kXcds = 8;                // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
+constexpr int kAppendXcdRun = 16;       // append: consecutive tiles of the list that one XCD takes in a row (one per CU)
 
 // Header words of the plan, at the start of the workspace.
 enum PlanWord { kPlanPer = 0, kPlanTotal = 1, kPlanWorkers = 2, kPlanRowsPerB = 3, kPlanTiles = 4, kPlanWords = 64 };

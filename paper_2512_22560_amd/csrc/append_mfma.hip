@@ -353,25 +353,37 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   // this phase no second wave hides the LDS latency.  After the step at schedule position pos the
   // caller's piece(pos) runs: the FP8 path threads its LDS writes between the MFMAs there.
   constexpr int kAhead = 4;
+  // bf16 pools: the operands of the first kAhead steps of a phase that starts with the second product are
+  // read at the end of the vector phase before it, in front of the barrier (the V tile they come from was
+  // complete one phase earlier), so that the phase does not open with an LDS round trip.
+  constexpr bool kEarly = !FP8;
+  bf16x8 early[kAhead];
+  typedef __attribute__((address_space(3))) shortx4 lds_s4;
+  auto read_v_operand = [&](const unsigned char* vbuf, auto t_c, bf16x8& dst) __attribute__((always_inline)) {
+    constexpr int t = decltype(t_c)::value;
+    constexpr int sub = t >> 3, ks = (t >> 2) & 1, dt = t & 3;
+    if constexpr (dt < kDT) {
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const shortx4 raw = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s4*)(vbuf + (sub * 32 + ks * 16 + hf * 4) * kRowBytes + voff[dt]));
+        const bf16x4 h4 = __builtin_bit_cast(bf16x4, raw);
+        dst[hf * 4 + 0] = h4[0]; dst[hf * 4 + 1] = h4[1]; dst[hf * 4 + 2] = h4[2]; dst[hf * 4 + 3] = h4[3];
+      }
+    }
+  };
+  auto read_early = [&](int vbo) __attribute__((always_inline)) {
+    static_for<kAhead>([&](auto t_c) __attribute__((always_inline)) { read_v_operand(v_lds[0] + vbo, t_c, early[decltype(t_c)::value]); });
+  };
   auto matrix_phase = [&](auto first_c, auto last_c, int kbo, int vbo, auto&& piece) __attribute__((always_inline)) {
     constexpr int T0 = decltype(first_c)::value, T1 = decltype(last_c)::value;
     const unsigned char* kbuf = k_lds[0] + kbo;    // byte offsets of the ring slots
     const unsigned char* vbuf = v_lds[0] + vbo;
-    typedef __attribute__((address_space(3))) shortx4 lds_s4;
     bf16x8 ops[32];
     auto fetch = [&](auto t_c) __attribute__((always_inline)) {
       constexpr int t = decltype(t_c)::value;
       if constexpr (t < 16) {
-        constexpr int sub = t >> 3, ks = (t >> 2) & 1, dt = t & 3;
-        if constexpr (dt < kDT) {
-#pragma unroll
-          for (int hf = 0; hf < 2; ++hf) {
-            const shortx4 raw = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_s4*)(vbuf + (sub * 32 + ks * 16 + hf * 4) * kRowBytes + voff[dt]));
-            const bf16x4 h4 = __builtin_bit_cast(bf16x4, raw);
-            ops[t][hf * 4 + 0] = h4[0]; ops[t][hf * 4 + 1] = h4[1]; ops[t][hf * 4 + 2] = h4[2]; ops[t][hf * 4 + 3] = h4[3];
-          }
-        }
+        read_v_operand(vbuf, t_c, ops[t]);
       } else {
         constexpr int u = t - 16, kk = u >> 1, sub = u & 1;
         if constexpr (kk < kKK) ops[t] = *(const bf16x8*)(kbuf + sub * 32 * kRowBytes + koff[kk]);
@@ -401,7 +413,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     };
     static_for<kAhead>([&](auto d_c) __attribute__((always_inline)) {
       constexpr int t = T0 + decltype(d_c)::value;
-      if constexpr (t < T1) fetch(std::integral_constant<int, t>{});
+      if constexpr (kEarly && T0 == 0) ops[t] = early[t];
+      else if constexpr (t < T1) fetch(std::integral_constant<int, t>{});
     });
     __builtin_amdgcn_sched_barrier(0);
     static_for<32>([&](auto t_c) __attribute__((always_inline)) {
@@ -595,12 +608,10 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
           dma(tile_addr(a.k_pages, 0, u0 + 1, tile_off_of(hh[u0 + 1][j]), j), k_lds[0] + (u0 + 1) * kTileBytes + wave * 1024 + j * kThreads * 16);
           dma(tile_addr(a.v_pages, 1, u0, tile_off_of(hh[u0][j]), j), v_lds[0] + u0 * kTileBytes + wave * 1024 + j * kThreads * 16);
         }
-      DMA_WAIT(kLead * 2 * kLoads);                  // K block 0 has landed
+      DMA_WAIT((kLead - 1) * 2 * kLoads);            // K block 0 and unit 0 have landed (unit 0 is read early, one barrier from now)
     }
     PHASE_END();
     if (grp == 1) {                                  // the trailing half starts one phase late
-      // ... and the leading half reads unit 0 in phase 2, before the trailing half's first vector phase ends
-      if constexpr (!FP8) DMA_WAIT((kLead - 1) * 2 * kLoads);
       PHASE_END();
     }
 #pragma unroll
@@ -711,6 +722,7 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
       scalar_issue(i);
       if constexpr (kActive) softmax(i);
       scalar_await();
+      if constexpr (kEarly && kActive) read_early(ko[0]);   // V block i, for the matrix phase that follows
       PHASE_END();
       next_block();
     };

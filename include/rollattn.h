@@ -262,6 +262,21 @@ int32_t rollattn_plan_workers(const rollattn_desc *desc);
 int rollattn_debug_read_plan(const rollattn_desc *desc, const void *workspace, int32_t *per_out,
                              int32_t *total_out, int32_t *starts_out, void *hip_stream);
 
+/* Copies the tile list that the last attn_append call (BF16 queries) left in `workspace` back to the host
+ * (synchronises the stream), for bit-exact tests of the append plan.  The rule: every chunk is cut into tiles of
+ * max(1, 256 / (Hq / Hkv)) query tokens counted from its first token; the list holds the trajectories by context
+ * length, longest first (equal lengths: lower index first; batches of more than 4096 trajectories: index order),
+ * and a chunk's tiles last tile first, because workgroups take the list in order and the expensive tiles should
+ * start first.  Writes the number of tiles and 2 int32 per tile, (b, first row of the tile in its chunk);
+ * tiles_out must hold 2 * rollattn_append_plan_capacity(desc, total_q) int32. */
+int rollattn_debug_read_append_plan(const rollattn_desc *desc, const void *workspace, int32_t total_q,
+                                    int32_t *n_tiles_out, int32_t *tiles_out, void *hip_stream);
+int32_t rollattn_append_plan_capacity(const rollattn_desc *desc, int32_t total_q);
+/* attn_step keeps its append tile list at this byte offset of its workspace (the decode part comes first):
+ * rollattn_debug_read_append_plan(desc, (char *)workspace + offset, ...) reads the list of a mixed step, in which
+ * chunks of one token are decode rows and contribute no tile. */
+size_t rollattn_step_append_offset(const rollattn_desc *desc);
+
 /* Optional per-kernel timing.  While enabled, attn_decode / attn_append / kv_write bracket their
  * main kernel (not the planning or merge kernels) with HIP events on the call's stream;
  * rollattn_profile_read synchronises those events and returns up to `cap` durations in

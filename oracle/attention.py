@@ -288,11 +288,25 @@ def split_plan(ctx_lens, rows_per_b, workers, block_tokens=32):
     return per, total, starts, np.asarray(segments, dtype=np.int32).reshape(-1, 6)
 
 
-def append_tile_plan(q_lens, tile_tokens):
-    """Append work list: each chunk is cut into tiles of tile_tokens query tokens (the
-    last ragged).  Returns int32 [n_tiles, 3] of (b, first_row_in_chunk, rows)."""
+def append_tile_plan(q_lens, ctx_lens, tile_tokens, rank_limit=4096, skip_unit_chunks=False):
+    """Append work list, in the order the workgroups take it.  Each chunk is cut into tiles of
+    tile_tokens query tokens counted from its first token (so only its last tile can be short).
+    A tile's cost grows with the context of its trajectory and with its position in the chunk, and
+    tiles are handed out in list order, so the list starts with the expensive ones: trajectories by
+    context length, longest first (equal lengths: lower index first), and within a chunk the last
+    tile first.  Batches of more than rank_limit trajectories are listed in index order instead.
+    With skip_unit_chunks (the mixed step, where one-token chunks are decode rows) chunks of one
+    token contribute no tile.  Returns int32 [n_tiles, 3] of (b, first row in the chunk, rows)."""
+    q = np.asarray(q_lens, dtype=np.int64).tolist()
+    ctx = np.asarray(ctx_lens, dtype=np.int64).tolist()
+    order = list(range(len(q)))
+    if len(q) <= rank_limit:
+        order.sort(key=lambda b: (-ctx[b], b))
     tiles = []
-    for b, n in enumerate(np.asarray(q_lens, dtype=np.int64).tolist()):
-        for start in range(0, n, tile_tokens):
-            tiles.append((b, start, min(tile_tokens, n - start)))
+    for b in order:
+        if skip_unit_chunks and q[b] == 1:
+            continue
+        starts = list(range(0, q[b], tile_tokens))
+        for start in reversed(starts):
+            tiles.append((b, start, min(tile_tokens, q[b] - start)))
     return np.asarray(tiles, dtype=np.int32).reshape(-1, 3)

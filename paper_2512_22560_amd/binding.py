@@ -23,7 +23,7 @@ EXPORTS = (
     "kv_write", "rollattn_workspace_bytes",
     "rollattn_step_workspace_bytes", "rollattn_shared_workspace_bytes", "rollattn_debug_gather",
     "rollattn_debug_check_inputs",
-    "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan",
+    "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan", "rollattn_debug_read_append_plan", "rollattn_append_plan_capacity", "rollattn_step_append_offset",
     "rollattn_profile_enable", "rollattn_profile_read", "rollattn_status_string",
     "rollattn_last_hip_error", "rollattn_version",
 )
@@ -101,6 +101,12 @@ def lib() -> ctypes.CDLL:
         l.rollattn_plan_workers.restype = ctypes.c_int32
         l.rollattn_debug_read_plan.argtypes = [dp, vp, i32p, i32p, i32p, vp]
         l.rollattn_debug_read_plan.restype = ctypes.c_int
+        l.rollattn_debug_read_append_plan.argtypes = [dp, vp, i32, i32p, i32p, vp]
+        l.rollattn_debug_read_append_plan.restype = ctypes.c_int
+        l.rollattn_append_plan_capacity.argtypes = [dp, i32]
+        l.rollattn_append_plan_capacity.restype = ctypes.c_int32
+        l.rollattn_step_append_offset.argtypes = [dp]
+        l.rollattn_step_append_offset.restype = ctypes.c_size_t
         l.rollattn_profile_enable.argtypes = [ctypes.c_int]
         l.rollattn_profile_enable.restype = ctypes.c_int
         l.rollattn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int]
@@ -377,6 +383,20 @@ def read_plan(desc: Desc, workspace: torch.Tensor, stream=None):
     if rc:
         raise RollattnError(rc, "rollattn_debug_read_plan")
     return int(per.value), int(total.value), starts
+
+
+def read_append_plan(desc: Desc, workspace: torch.Tensor, total_q: int, stream=None) -> np.ndarray:
+    """The tile list the last attn_append call left in `workspace`: int32 [n_tiles, 2] of (b, first row in the chunk)."""
+    l = lib()
+    cap = int(l.rollattn_append_plan_capacity(ctypes.byref(desc), int(total_q)))
+    tiles = np.zeros((max(cap, 1), 2), dtype=np.int32)
+    n = ctypes.c_int32(0)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    rc = l.rollattn_debug_read_append_plan(ctypes.byref(desc), _ptr(workspace), int(total_q), ctypes.byref(n),
+                                           tiles.ctypes.data_as(i32p), _stream(stream))
+    if rc:
+        raise RollattnError(rc, "rollattn_debug_read_append_plan")
+    return tiles[: n.value].copy()
 
 
 def profile_enable(on: bool) -> None:

@@ -235,6 +235,36 @@ int rollattn_debug_read_plan(const rollattn_desc* desc, const void* workspace, i
   return ROLLATTN_OK;
 }
 
+int32_t rollattn_append_plan_capacity(const rollattn_desc* desc, int32_t total_q) {
+  if (check_desc(desc, false) != ROLLATTN_OK || total_q < 0) return 0;
+  return append_layout(*desc, total_q).workers;
+}
+
+int rollattn_debug_read_append_plan(const rollattn_desc* desc, const void* workspace, int32_t total_q, int32_t* n_tiles_out,
+                                    int32_t* tiles_out, void* hip_stream) {
+  int rc = check_desc(desc, false);
+  if (rc) return rc;
+  if (!workspace || !n_tiles_out || !tiles_out || total_q < 0) return ROLLATTN_EINVAL;
+  const WorkspaceLayout w = append_layout(*desc, total_q);
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return fail_hip(e);
+  const char* base = (const char*)workspace;
+  int32_t header[kPlanWords];
+  std::vector<int32_t> tb((size_t)w.workers), tq((size_t)w.workers);
+  e = hipMemcpy(header, base + w.header, sizeof(header), hipMemcpyDeviceToHost);
+  if (e == hipSuccess) e = hipMemcpy(tb.data(), base + w.wstart, sizeof(int32_t) * tb.size(), hipMemcpyDeviceToHost);
+  if (e == hipSuccess) e = hipMemcpy(tq.data(), base + w.tile_q0, sizeof(int32_t) * tq.size(), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail_hip(e);
+  const int32_t n = std::max(0, std::min(header[kPlanTiles], w.workers));
+  *n_tiles_out = n;
+  for (int32_t i = 0; i < n; ++i) {
+    tiles_out[2 * i] = tb[i];
+    tiles_out[2 * i + 1] = tq[i];
+  }
+  return ROLLATTN_OK;
+}
+
 int32_t rollattn_plan_workers(const rollattn_desc* desc) {
   if (check_desc(desc, false) != ROLLATTN_OK) return 0;
   return decode_layout(*desc).workers;
@@ -466,6 +496,11 @@ int attn_merge(const rollattn_desc* desc, int64_t rows, const void* o1, const fl
 size_t rollattn_step_workspace_bytes(const rollattn_desc* desc, int32_t total_q) {
   if (check_desc(desc) != ROLLATTN_OK || total_q < 0) return 0;
   return align256(decode_layout(*desc).total) + append_layout(*desc, total_q).total;
+}
+
+size_t rollattn_step_append_offset(const rollattn_desc* desc) {
+  if (check_desc(desc, false) != ROLLATTN_OK) return 0;
+  return align256(decode_layout(*desc).total);
 }
 
 int attn_step(const rollattn_desc* desc, const void* q, const int32_t* q_lens, const int32_t* q_offsets, int32_t total_q,

@@ -1,6 +1,7 @@
 """Full-size parity: the four benchmark workloads exactly as bench.py launches them (same batches,
-same entry points, same workspace sizing), checked against the oracle on sampled trajectories that
-the oracle can afford one by one: the shortest, the longest and a few seeded random ones."""
+same entry points, same workspace sizing), checked against the oracle on what it can afford one by one:
+for decode sampled trajectories (the shortest, the longest and a few seeded random ones), for append
+sampled rows of the shortest, the median and the longest trajectory and of a few random ones."""
 import numpy as np
 import pytest
 import torch
@@ -13,7 +14,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _sample(batch, n_random, seed, cost=None, budget=None):
+def _sample(batch, n_random, seed):
     lens = batch.ctx_lens_host
     rows = {int(np.argmin(lens)), int(np.argmax(lens))}
     rng = np.random.default_rng(seed)
@@ -21,21 +22,34 @@ def _sample(batch, n_random, seed, cost=None, budget=None):
         if len(rows) >= n_random + 2:
             break
         rows.add(int(r))
-    rows = sorted(rows)
-    if cost is not None:                       # keep the oracle's work bounded
-        rows = sorted(rows, key=lambda r: cost[r])
-        keep, spent = [], 0
-        for r in rows:
-            if not keep or spent + cost[r] <= budget:
-                keep.append(r)
-                spent += cost[r]
-        rows = sorted(keep)
-    return np.asarray(rows)
+    return np.asarray(sorted(rows))
 
 
-def _rows_of(batch, rows):
+def _check_sampled_chunk_rows(batch, out, seed, what):
+    """Append parity at full size on sampled rows.  Row i of a chunk equals a decode step at context
+    L - n + i + 1, which is what the oracle computes, one row at a time: the first and last rows, the rows
+    on either side of every kind of tile edge and seeded random rows of the trajectories with the shortest, the
+    median and the longest context (the longest is the one with the most blocks, tiles and ring wraps in the
+    launch that the bench times) and of a few seeded random trajectories."""
+    from oracle import attention as O
+    from tests.helpers import oracle_args
+    w = batch.workload
+    tile_tokens = max(1, 256 // (w.num_q_heads // w.num_kv_heads))
+    rng = np.random.default_rng(seed)
     offs = np.concatenate([[0], np.cumsum(batch.q_lens_host)])
-    return np.concatenate([np.arange(offs[r], offs[r + 1]) for r in rows])
+    order = np.argsort(batch.ctx_lens_host, kind="stable")
+    trajs = [int(order[0]), int(order[len(order) // 2]), int(order[-1])] + rng.choice(len(order), 3, replace=False).tolist()
+    args = oracle_args(batch)
+    q, pt = W.raw_numpy(batch.q), args["page_table"]
+    qs, tables, lens, idx = [], [], [], []
+    for traj in dict.fromkeys(trajs):
+        n, L = int(batch.q_lens_host[traj]), int(batch.ctx_lens_host[traj])
+        picks = [0, 1, tile_tokens - 1, tile_tokens, 2 * tile_tokens - 1, n // 2, n - tile_tokens, n - 2, n - 1] + rng.integers(0, n, 5).tolist()
+        for i in sorted(set(i for i in picks if 0 <= i < n)):
+            qs.append(q[offs[traj] + i]); tables.append(pt[traj]); lens.append(L - n + i + 1); idx.append(int(offs[traj] + i))
+    ref = O.attn_decode(np.stack(qs), args["k_pages"], args["v_pages"], np.stack(tables), np.asarray(lens), sm_scale=args["sm_scale"],
+                        q_dtype=args["q_dtype"], kv_dtype=args["kv_dtype"], k_scale=args["k_scale"], v_scale=args["v_scale"])
+    check(out[torch.tensor(idx, device=DEV)], ref, "bf16", f"{what}: {len(idx)} rows of trajectories {list(dict.fromkeys(trajs))}")
 
 
 @pytest.mark.parametrize("c", [2, 3])
@@ -55,11 +69,7 @@ def test_append_workload_full_size():
     out = gpu_append(b)
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
-    cost = b.q_lens_host * b.ctx_lens_host
-    rows = _sample(b, 3, seed=4, cost=cost, budget=2.0e7)
-    sub = b.select(rows)
-    ref = oracle_append(sub)
-    check(out[torch.from_numpy(_rows_of(b, rows)).to(DEV)], ref, "bf16", f"config 4 rows {rows.tolist()}")
+    _check_sampled_chunk_rows(b, out, seed=4, what="config 4")
 
 
 def test_mixed_step_full_size():
@@ -72,10 +82,7 @@ def test_mixed_step_full_size():
     rows = _sample(dec, 6, seed=5)
     check(out_d[torch.from_numpy(rows).to(DEV)], oracle_decode(dec.select(rows)), "bf16",
           f"config 5 decode rows {rows.tolist()}")
-    cost = app.q_lens_host * app.ctx_lens_host
-    rows = _sample(app, 2, seed=6, cost=cost, budget=6.0e6)
-    check(out_a[torch.from_numpy(_rows_of(app, rows)).to(DEV)], oracle_append(app.select(rows)), "bf16",
-          f"config 5 append rows {rows.tolist()}")
+    _check_sampled_chunk_rows(app, out_a, seed=6, what="config 5 append")
 
 
 def test_workspace_is_sized_from_the_descriptor_alone():

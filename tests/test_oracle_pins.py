@@ -387,6 +387,37 @@ def test_split_plan_covers_every_block_once_in_equal_runs():
         assert all(starts[w][0] == -1 for w in range(len(by_worker), workers))
 
 
+def test_append_tile_plan_covers_every_chunk_row_once_most_expensive_tiles_first():
+    rng = np.random.default_rng(6)
+    cases = [(rng.integers(0, 300, 40), 64, False), (rng.integers(0, 40, 25), 16, True), (np.array([0, 1, 1, 0, 5]), 4, True),
+             (np.array([7]), 1, False), (np.zeros(6, dtype=np.int64), 16, False), (rng.integers(1, 9, 30), 256, False)]
+    for q_lens, tile_tokens, skip_unit in cases:
+        ctx = q_lens + rng.integers(0, 5000, len(q_lens))
+        ctx[: len(ctx) // 3] = ctx[0]                                # ties in the ranking
+        tiles = O.append_tile_plan(q_lens, ctx, tile_tokens, skip_unit_chunks=skip_unit)
+        covered = {b: [] for b in range(len(q_lens))}
+        for b, start, rows in tiles.tolist():
+            assert 0 < rows <= tile_tokens and start % tile_tokens == 0 and start + rows <= q_lens[b]
+            assert rows == tile_tokens or start + rows == q_lens[b]  # only a chunk's last tile is short
+            covered[b].extend(range(start, start + rows))
+        for b, n in enumerate(q_lens.tolist()):
+            want = [] if (skip_unit and n == 1) else list(range(n))
+            assert sorted(covered[b]) == want                        # every row of every chunk exactly once
+        # cost order: contexts never increase along the list, a trajectory's tiles are adjacent, last tile first
+        bs = tiles[:, 0].tolist()
+        assert all(ctx[bs[i]] >= ctx[bs[i + 1]] for i in range(len(bs) - 1))
+        assert all(bs[i] < bs[i + 1] for i in range(len(bs) - 1) if bs[i] != bs[i + 1] and ctx[bs[i]] == ctx[bs[i + 1]])
+        firsts = [i for i in range(len(bs)) if i == 0 or bs[i] != bs[i - 1]]
+        assert len(firsts) == len(set(bs))
+        for i in range(len(bs) - 1):
+            if bs[i] == bs[i + 1]:
+                assert tiles[i, 1] == tiles[i + 1, 1] + tile_tokens
+    # beyond the ranking limit the list is in index order
+    q_lens = rng.integers(0, 3, 50)
+    tiles = O.append_tile_plan(q_lens, rng.integers(2, 99, 50), 2, rank_limit=49)
+    assert tiles[:, 0].tolist() == sorted(tiles[:, 0].tolist())
+
+
 # ---------------------------------------------------------------- softmax denominators and the merge of two ranges
 
 def _lse_single(q, k, **kw):

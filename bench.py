@@ -5,23 +5,33 @@
 
 A step is one pass of the whole attention path over one synthetic batch that is already
 resident in HBM: the device-side plan, the main kernel and (decode) the split-K merge.  The
-headline workload is the mid-size bf16 decode batch; the long-tail decode, the
-observation-append batch, the mixed FP8 rollout step and the KV-recomputation prefill (append
-with an empty prefix over whole histories) and the KV write of the append chunks (bf16 and FP8
-pools) and the decode step of grouped rollouts that share an 8k prompt (with the prompt read once
-per group, and plain decode on the same aliased tables for comparison) are timed after it and
-reported in the same JSON line under "workloads".  Every figure is throughput on ALGORITHMIC bytes /
-flops (K and V of each KV head once per call, live page-table entries, page scales, Q in,
-O out; 4*Hq*D flops per attended pair), never on what the kernels happen to move.
+headline workload is the mid-size bf16 decode batch (the slowest of the decode workloads
+relative to its roofline); the long-tail decode, the observation-append batch, the mixed FP8
+rollout step, the KV-recomputation prefill (append with an empty prefix over whole histories),
+the KV write of the append chunks (bf16 and FP8 pools) and the decode step of grouped rollouts
+that share an 8k prompt (with the prompt read once per group, and plain decode on the same
+aliased tables for comparison) are timed after it and reported in the same JSON line under
+"workloads".  Every figure is throughput on ALGORITHMIC bytes / flops (K and V of each KV head
+once per call, live page-table entries, page scales, Q in, O out; 4*Hq*D flops per attended
+pair), never on what the kernels happen to move.
 
-The "roofline" object is for the main kernel of the headline workload, timed with HIP events
-that the library records around that kernel on the call's stream.  "cpu_baseline" is the
-float64 oracle, untuned, on the host cores of the same box, on the same bytes.
+Timing.  `ms_per_step` is wall time over exactly --steps steps between two device
+synchronisations.  A second pass of the same number of steps brackets every call with events on
+the call's stream and lets the library bracket its main kernel: the per-leg kernel and
+whole-call figures (mean, median, minimum) all come from that one pass.  Fractions are given
+against the nominal peaks (HBM 8 TB/s, dense bf16 MFMA 2.5 PFLOP/s) and against what two
+microbenchmarks of libbench_peaks.so reach on this GPU in this run (a streaming read of 4 GiB
+and a register-resident MFMA loop).
+
+The "roofline" object is for the main kernel of the headline workload.  "cpu_baseline" is the
+float64 oracle, untuned, on the host cores of the same box, on the same bytes;
+"cpu_baseline_append" is the same for a bounded sample of the append workload.
 """
 from __future__ import annotations
 
 import argparse
 import ctypes
+import hashlib
 import json
 import os
 import sys
@@ -36,11 +46,37 @@ METRIC = "decode-attn achieved HBM GB/s (% of peak) + append TFLOP/s, ragged pag
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 HEADLINE = 2
-# HBM bytes per launch of the headline workload's main kernel, from hardware counters (FETCH_SIZE and
-# WRITE_SIZE, each scaled by its reading on a copy of known size; profiles/decode_mfma_c2_decode_bf16_b64.md
-# has the commands and the raw readings).  Valid for the decode kernel as committed with that profile:
-# set to None when the kernel changes, until the counters have been taken again.
-HEADLINE_TRAFFIC_BYTES = {"decode_mfma_kernel": 814_387_200 + 5_121_024}
+# HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, each scaled by its
+# reading on a copy of known size).  They cannot be taken inside this program; profiles/hbm_traffic.json keeps
+# them together with the hashes of the kernel sources they were taken with, and a figure is reported only while
+# those sources are unchanged.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+CSRC = os.path.join(ROOT, "paper_2512_22560_amd", "csrc")
+MAIN_KERNEL_SOURCES = {"decode": ["decode_mfma.hip", "rollattn_internal.h"], "append": ["append_mfma.hip", "rollattn_internal.h"]}
+
+
+def source_hash(files):
+    h = hashlib.sha256()
+    for f in files:
+        with open(os.path.join(CSRC, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def counter_traffic(workload_name, kind):
+    """HBM bytes per launch of this workload's main kernel from the committed counter readings, or None when there
+    are none or the kernel's sources have changed since they were taken."""
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            table = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    entry = table.get(f"{workload_name}:{kind}")
+    if not entry or kind not in MAIN_KERNEL_SOURCES:
+        return None
+    if entry.get("source_hash") != source_hash(MAIN_KERNEL_SOURCES[kind]):
+        return None
+    return int(entry["fetch_bytes"]) + int(entry["write_bytes"])
 
 
 def _parts(batch, c, W):
@@ -135,7 +171,9 @@ class Leg:
 
 
 def time_legs(legs, steps, warmup, B):
-    """Wall time per step over exactly `steps` steps, then per-leg main-kernel time from HIP events."""
+    """ms per step (wall, over exactly `steps` steps), the same through a HIP graph, then one more pass of `steps`
+    steps in which every call is bracketed by events on its stream and the library brackets its main kernel:
+    per leg (kernel ms per call [steps], whole-call ms per call [steps])."""
     import torch
     for _ in range(warmup):
         for leg in legs:
@@ -178,42 +216,106 @@ def time_legs(legs, steps, warmup, B):
         del graph
     except Exception as e:      # reported, never fatal: the eager figures above are the contract
         print(f"bench.py: graph replay skipped: {e}", file=sys.stderr)
-    kernel_ms = []
-    for leg in legs:
-        B.profile_enable(True)
-        for _ in range(steps):
+    # the profiled pass: kernel and whole-call durations of the same calls
+    B.profile_enable(True)
+    B.profile_read()
+    marks = [[] for _ in legs]
+    for _ in range(steps):
+        for li, leg in enumerate(legs):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
             leg.step()
-        torch.cuda.synchronize()
-        kernel_ms.append(B.profile_read())
-        B.profile_enable(False)
-    return ms_per_step, kernel_ms, graph_ms
+            b.record()
+            marks[li].append((a, b))
+    torch.cuda.synchronize()
+    kernel_all = B.profile_read()
+    B.profile_enable(False)
+    per_step = sum(2 if leg.kind in ("decode_shared", "step") else 1 for leg in legs)   # main kernels per step, in launch order
+    kernel_all = np.asarray(kernel_all[: len(kernel_all) // per_step * per_step]).reshape(-1, per_step)
+    out, col = [], 0
+    for li, leg in enumerate(legs):
+        n = 2 if leg.kind in ("decode_shared", "step") else 1   # two main kernels per call (shared and private half; chunks and decode rows): their sum
+        kms = kernel_all[:, col:col + n].sum(axis=1)
+        col += n
+        call = np.asarray([a.elapsed_time(b) for a, b in marks[li]])
+        out.append((kms, call))
+    return ms_per_step, out, graph_ms
 
 
-def leg_report(leg, kms):
-    if leg.kind in ("decode_shared", "step"):  # two main kernels per call (shared and private half; chunks and decode rows): their sum
-        kms = np.asarray(kms)[: len(kms) // 2 * 2].reshape(-1, 2).sum(axis=1)
-    avg = float(np.mean(kms))
+def _stats(x):
+    return {"avg": float(np.mean(x)), "median": float(np.median(x)), "min": float(np.min(x))}
+
+
+def leg_report(leg, kms, call_ms, peaks, step_ms=None):
+    """step_ms: wall time per step of a workload with this one leg (then the whole-call figure is taken from it:
+    the events around a call cost a few microseconds themselves, which matters for the short decode calls)."""
+    k, c = _stats(kms), _stats(call_ms)
     work = leg.work
-    if leg.kind in ("decode", "kv_write", "decode_shared", "decode_aliased"):
-        ach = work["bytes"] / avg / 1e6
-        return {"kind": leg.kind, "bound": "hbm", "kernel_ms_avg": avg, "kernel_ms_min": float(np.min(kms)),
-                "algorithmic_bytes": work["bytes"], "achieved": ach, "unit": "GB/s", "peak": HBM_PEAK_GBS,
-                "frac": ach / HBM_PEAK_GBS}
-    ach = work["flops"] / avg / 1e9
-    return {"kind": leg.kind, "bound": "mfma", "kernel_ms_avg": avg, "kernel_ms_min": float(np.min(kms)),
-            "algorithmic_flops": work["flops"], "algorithmic_bytes": work["bytes"], "achieved": ach,
-            "unit": "TFLOP/s", "peak": MFMA_BF16_PEAK_TFLOPS, "frac": ach / MFMA_BF16_PEAK_TFLOPS}
+    hbm = leg.kind in ("decode", "kv_write", "decode_shared", "decode_aliased")
+    amount = work["bytes"] if hbm else work["flops"]
+    unit, peak, scale = ("GB/s", HBM_PEAK_GBS, 1e6) if hbm else ("TFLOP/s", MFMA_BF16_PEAK_TFLOPS, 1e9)
+    ach = amount / k["avg"] / scale
+    rep = {"kind": leg.kind, "bound": "hbm" if hbm else "mfma",
+           "kernel_ms_avg": k["avg"], "kernel_ms_median": k["median"], "kernel_ms_min": k["min"],
+           "call_ms_avg": c["avg"], "call_ms_median": c["median"], "call_ms_min": c["min"],
+           "algorithmic_bytes": work["bytes"], "achieved": ach, "unit": unit, "peak": peak, "frac": ach / peak,
+           "achieved_median": amount / k["median"] / scale, "frac_median": amount / k["median"] / scale / peak,
+           # the whole call (plan + main kernel + merge), from the events around it in the same pass
+           "call_achieved": amount / (step_ms or c["avg"]) / scale, "call_frac": amount / (step_ms or c["avg"]) / scale / peak,
+           "call_frac_from": "wall time per step" if step_ms else "events around the call"}
+    if not hbm:
+        rep["algorithmic_flops"] = work["flops"]
+    measured = (peaks or {}).get("hbm_read_GBs" if hbm else "mfma_bf16_TFLOPs")
+    if measured:
+        rep["frac_of_measured_peak"] = ach / measured
+    return rep
 
 
-def cpu_baseline(batch, W, budget_s=20.0):
-    """The oracle as it stands, on the host cores, on the same stored bytes (headline workload)."""
+def measure_peaks(dev):
+    """What this GPU delivers at best in this run: a streaming read of 4 GiB, and a register-resident loop of the
+    append kernel's matrix instruction.  Both kernels live in libbench_peaks.so, outside the library."""
     import torch
-    from oracle import attention as O
+    from paper_2512_22560_amd import build as lib_build
+    if not os.path.exists(lib_build.PEAKS_LIB):
+        return None
+    lib = ctypes.CDLL(lib_build.PEAKS_LIB)
+    vp = ctypes.c_void_p
+    lib.peaks_stream_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_float), vp]
+    lib.peaks_mfma_bf16.argtypes = [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double), vp]
+    nbytes = 4 << 30
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    buf.view(torch.int32).random_(0, 1 << 30)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ms = ctypes.c_float(0)
+    rc = lib.peaks_stream_read(vp(buf.data_ptr()), nbytes, 5, vp(sink.data_ptr()), ctypes.byref(ms), stream)
+    if rc:
+        raise RuntimeError(f"peaks_stream_read: HIP error {rc}")
+    read_gbs = nbytes / ms.value / 1e6
+    flops = ctypes.c_double(0)
+    rc = lib.peaks_mfma_bf16(20000, vp(sink.data_ptr()), ctypes.byref(ms), ctypes.byref(flops), stream)
+    if rc:
+        raise RuntimeError(f"peaks_mfma_bf16: HIP error {rc}")
+    del buf
+    torch.cuda.empty_cache()
+    return {"hbm_read_GBs": read_gbs, "hbm_read_frac_of_nominal": read_gbs / HBM_PEAK_GBS,
+            "mfma_bf16_TFLOPs": flops.value / ms.value / 1e9, "mfma_bf16_frac_of_nominal": flops.value / ms.value / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+            "how": "streaming read of 4 GiB (16-byte loads, 5 passes); v_mfma_f32_32x32x16_bf16 on register operands, 8 waves per CU x 4 chains"}
+
+
+def _blas_threads():
     try:
         from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] + [1]))
     except Exception:
-        threads = os.cpu_count() or 1
+        return int(os.cpu_count() or 1)
+
+
+def cpu_baseline(batch, W, budget_s=15.0):
+    """The oracle as it stands, on the host cores, on the same stored bytes (decode workload)."""
+    from oracle import attention as O
+    threads = _blas_threads()
     w = batch.workload
     args = dict(k_pages=W.raw_numpy(batch.k_pages), v_pages=W.raw_numpy(batch.v_pages),
                 page_table=W.raw_numpy(batch.page_table), sm_scale=w.sm_scale, q_dtype=w.q_dtype,
@@ -232,9 +334,55 @@ def cpu_baseline(batch, W, budget_s=20.0):
     O.attn_decode(q[rows], **dict(args, page_table=args["page_table"][rows], ctx_lens=batch.ctx_lens_host[rows]))
     dt = time.perf_counter() - t0
     work = W.algorithmic_work(w, batch.ctx_lens_host[rows], np.ones(n, dtype=np.int64))
-    return {"value": work["bytes"] / dt / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+    return {"value": work["bytes"] / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"{n} of {len(order)} trajectories of {w.name} ({int(batch.ctx_lens_host[rows].sum())} tokens), "
                       f"numpy float64 oracle, {dt:.1f} s", "seconds": dt}
+
+
+def cpu_baseline_append(batch, W, budget_s=15.0):
+    """The oracle on a bounded, seeded sample of an append workload's trajectories (the shortest context, then
+    random ones while the budget lasts); the time for the whole batch is extrapolated by attended pairs."""
+    from oracle import attention as O
+    threads = _blas_threads()
+    w = batch.workload
+
+    def pairs(rows):
+        n, L = batch.q_lens_host[rows].astype(np.int64), batch.ctx_lens_host[rows].astype(np.int64)
+        return int((n * (L - n) + n * (n + 1) // 2).sum())
+
+    def run(rows):
+        sub = batch.select(np.asarray(rows))
+        t0 = time.perf_counter()
+        O.attn_append(W.raw_numpy(sub.q), sub.q_lens_host, k_pages=W.raw_numpy(sub.k_pages), v_pages=W.raw_numpy(sub.v_pages),
+                      page_table=W.raw_numpy(sub.page_table), ctx_lens=sub.ctx_lens_host, sm_scale=w.sm_scale, q_dtype=w.q_dtype,
+                      kv_dtype=w.kv_dtype, k_scale=W.raw_numpy(sub.k_scale), v_scale=W.raw_numpy(sub.v_scale))
+        return time.perf_counter() - t0
+
+    cost = batch.q_lens_host * batch.ctx_lens_host
+    cheapest = int(np.argmin(np.where(batch.q_lens_host > 0, cost, cost.max() + 1)))
+    probe = run([cheapest])
+    rate = pairs([cheapest]) / max(probe, 1e-6)                      # attended pairs per second, first estimate
+    order = [r for r in np.random.default_rng(0).permutation(len(cost)).tolist() if r != cheapest and batch.q_lens_host[r] > 0]
+    rows, dt = [cheapest], probe
+    for _ in range(2):                           # the first estimate comes from a small problem and is pessimistic: refine once
+        spent = 0.0
+        rows = [cheapest]
+        for r in order:
+            t = pairs([r]) / rate
+            if spent + t <= budget_s:
+                rows.append(r)
+                spent += t
+        rows = sorted(rows)
+        dt = run(rows)
+        if dt > 0.6 * budget_s:
+            break
+        rate = pairs(rows) / max(dt, 1e-6)
+    all_rows = np.arange(len(cost))
+    flops = 4 * w.num_q_heads * w.head_dim * pairs(rows)
+    return {"value": flops / dt / 1e9, "unit": "GFLOP/s", "cores": threads, "kind": "oracle", "extrapolated": True,
+            "sample": f"{len(rows)} of {len(cost)} trajectories of {w.name} ({pairs(rows)} of {pairs(all_rows)} attended pairs), "
+                      f"numpy float64 oracle, {dt:.1f} s; whole batch extrapolated by attended pairs",
+            "seconds": dt, "seconds_whole_batch_extrapolated": dt * pairs(all_rows) / max(1, pairs(rows))}
 
 
 def main():
@@ -242,8 +390,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4, c5, c5_one_call, recompute, kv_write_c4, kv_write_c5, shared_prompt or shared_prompt_plain (or `copy`: 1 GiB copy for counter calibration)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only", default=None, help="run a single workload: c2, c3, c4, c5, c5_one_call, recompute, kv_write_c4, kv_write_c5, shared_prompt or shared_prompt_plain; `peaks`: the two peak microbenchmarks alone; `copy`: 1 GiB copy for counter calibration")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baselines")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the peak microbenchmarks")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this library runs on one GPU; nothing here shards or communicates, so --gpus must be 1",
@@ -271,6 +420,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "copy", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": max(1, a.steps)}))
         return
+    peaks = None if a.no_peaks else measure_peaks(dev)
+    if a.only == "peaks":
+        print(json.dumps({"measured_peaks": peaks}))
+        return
     extra = {"recompute": W.RECOMPUTE, "kv_write_c4": W.CONFIGS[4], "kv_write_c5": W.CONFIGS[5], "c5_one_call": W.CONFIGS[5],
              "shared_prompt": W.SHARED_PROMPT, "shared_prompt_plain": W.SHARED_PROMPT}
     if a.only:
@@ -279,15 +432,18 @@ def main():
         selected = [HEADLINE, 3, 4, 5, "c5_one_call", "recompute", "kv_write_c4", "kv_write_c5", "shared_prompt", "shared_prompt_plain"]
     reports = {}
     headline = None
-    cpu = None
+    cpu = cpu_app = None
     for c in selected:
         w = extra[c] if c in extra else W.CONFIGS[c]
         batch = W.build(w, dev)
         small = W.algorithmic_work(w, batch.ctx_lens_host, batch.q_lens_host)["kv_bytes"] < 2e9
         legs = [Leg(kind, bb, B, W, n_pools=3 if small else 1) for kind, bb in _parts(batch, c, W)]
-        steps = a.steps if c == selected[0] else max(5, min(a.steps, 20))
-        ms, kms, gms = time_legs(legs, steps, a.warmup, B)
-        rep = {"ms_per_step": ms, "graph_ms_per_step": gms, "steps": steps, "legs": [leg_report(l, k) for l, k in zip(legs, kms)],
+        ms, timed, gms = time_legs(legs, a.steps, a.warmup, B)
+        leg_reps = [leg_report(l, k, call, peaks, ms if len(legs) == 1 else None) for l, (k, call) in zip(legs, timed)]
+        for l, r in zip(legs, leg_reps):
+            if r["kind"] in MAIN_KERNEL_SOURCES:
+                r["hbm_traffic_bytes"] = counter_traffic(w.name, r["kind"])
+        rep = {"ms_per_step": ms, "graph_ms_per_step": gms, "steps": a.steps, "legs": leg_reps,
                "batch": w.batch, "heads": [w.num_q_heads, w.num_kv_heads, w.head_dim], "kv_dtype": w.kv_dtype,
                "tokens": int(batch.ctx_lens_host.sum()), "query_rows": int(batch.q_lens_host.sum())}
         reports[c if isinstance(c, str) and c != "recompute" else w.name] = rep
@@ -295,6 +451,8 @@ def main():
             headline = (w, rep, legs)
             if not a.no_cpu and c in (2, 3):
                 cpu = cpu_baseline(batch, W)
+        if c == 4 and not a.no_cpu:
+            cpu_app = cpu_baseline_append(batch, W)
         del legs, batch
         torch.cuda.empty_cache()
 
@@ -306,6 +464,13 @@ def main():
     else:
         value = legs[0].work["flops"] / rep["ms_per_step"] / 1e9
         unit = "TFLOP/s"
+    # the bar of the four benchmark configurations: decode legs against HBM, append legs against bf16 MFMA, kernel and whole call
+    targets = {}
+    for name, r in reports.items():
+        if name in ("c5_one_call",) or name.startswith(("kv_write", "shared_prompt", "recompute")):
+            continue
+        for l in r["legs"]:
+            targets[f"{name}:{l['kind']}"] = {"frac": l["frac"], "call_frac": l["call_frac"], "bar": 0.70 if l["bound"] == "hbm" else 0.50}
     line = {
         "metric": METRIC, "value": value, "unit": unit, "n_gpus": 1, "steps": rep["steps"], "warmup": a.warmup,
         "ms_per_step": rep["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -313,11 +478,14 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads,
                    "head_dim": w.head_dim, "page_size": 16, "kv_dtype": w.kv_dtype, "tokens": rep["tokens"]},
         "roofline": {"bound": lead["bound"], "achieved": lead["achieved"], "peak": lead["peak"], "unit": lead["unit"],
-                     "frac": lead["frac"],
-                     "traffic": HEADLINE_TRAFFIC_BYTES.get("decode_mfma_kernel") if (lead["kind"] == "decode" and w is W.CONFIGS[HEADLINE]) else None,
+                     "frac": lead["frac"], "traffic": lead.get("hbm_traffic_bytes"),
                      "kernel": "decode_mfma_kernel" if lead["kind"] == "decode" else "append_mfma_kernel",
-                     "kernel_ms_avg": lead["kernel_ms_avg"]},
+                     "kernel_ms_avg": lead["kernel_ms_avg"], "kernel_ms_median": lead["kernel_ms_median"],
+                     "frac_of_measured_peak": lead.get("frac_of_measured_peak")},
         "cpu_baseline": cpu,
+        "cpu_baseline_append": cpu_app,
+        "measured_peaks": peaks,
+        "targets": targets,
         "workloads": reports,
     }
     print(json.dumps(line))

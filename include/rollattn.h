@@ -21,7 +21,9 @@
  *
  * Memory.  All array arguments are DEVICE pointers unless marked "host".  The caller
  * owns every buffer; the library allocates nothing, frees nothing and keeps no state
- * between calls apart from the optional profiling events below.  Inputs are only
+ * between calls apart from the optional profiling events below (created by
+ * rollattn_profile_enable, never by an attention call) and the built-in scratch array of
+ * attn_decode_static.  Inputs are only
  * read; `out` and `workspace` are the only memory written (kv_write writes the pools and the
  * page scales instead).  Every device pointer must
  * be 16-byte aligned.  Layouts are dense row-major:
@@ -35,8 +37,8 @@
  *   v_scale       [num_pages] float             FP8 pools only: element = code * scale
  *                                               of its physical page (per pool)
  * Supported element types: q/out F32 with kv F32 (D = 64 or 128); q/out BF16 with kv
- * BF16 or FP8_E4M3 (OCP E4M3, no infinities, max 448; D = 64 or 128).  Accumulation
- * is float.  Hq / Hkv may be any positive integer (at most 256 for BF16 attn_append).
+ * BF16 or FP8_E4M3 (OCP E4M3, no infinities, max 448; D = 64 or 128; page scales must be
+ * positive and finite, as absmax / 448 is).  Accumulation is float.  Hq / Hkv may be any positive integer (at most 256 for BF16 attn_append).
  *
  * Execution.  Calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*,
  * NULL = the default stream) and return without synchronising; nothing is copied to
@@ -195,7 +197,8 @@ size_t rollattn_shared_workspace_bytes(const rollattn_desc *desc, int32_t group_
  * ctx_lens INCLUDES the new tokens, as in attn_append: new row i of trajectory b goes to position
  * L_b - n_b + i, page page_table[b][pos / 16], slot pos % 16, for every KV head.
  *   k_new, v_new [total_q][Hkv][D], elements of desc->q_dtype (F32 or BF16), rows packed in batch
- *   order as q_chunk is; q_offsets [B+1] their exclusive scan; max_q_len >= max n_b (host).
+ *   order as q_chunk is; q_offsets [B+1] their exclusive scan; max_q_len >= max n_b (host): it sizes
+ *   the launch, so rows of a chunk beyond an understated max_q_len would silently stay unwritten.
  *   Pools of the source type take the rows bit for bit.  FP8 pools (BF16 source) hold E4M3 codes
  *   times one float scale per physical page and pool, k_scale / v_scale [num_pages] (device, read
  *   and written here; desc->k_scale / v_scale are ignored).  Per page that receives new rows in
@@ -277,10 +280,12 @@ int32_t rollattn_append_plan_capacity(const rollattn_desc *desc, int32_t total_q
  * chunks of one token are decode rows and contribute no tile. */
 size_t rollattn_step_append_offset(const rollattn_desc *desc);
 
-/* Optional per-kernel timing.  While enabled, attn_decode / attn_append / kv_write bracket their
- * main kernel (not the planning or merge kernels) with HIP events on the call's stream;
- * rollattn_profile_read synchronises those events and returns up to `cap` durations in
- * milliseconds, oldest first, then forgets them.  At most 1024 launches are kept. */
+/* Optional per-kernel timing.  rollattn_profile_enable(1) creates a pool of 1024 HIP event pairs (the one place
+ * where the library creates anything, and only on request); while enabled, attn_decode / attn_append / kv_write
+ * bracket their main kernel (not the planning or merge kernels) with a pair from the pool on the call's stream,
+ * as long as pairs are left and the stream is not being captured into a graph (events recorded during a capture
+ * cannot be read back, so such calls record nothing).  rollattn_profile_read synchronises the recorded events,
+ * returns up to `cap` durations in milliseconds, oldest first, and makes the pairs available again. */
 int rollattn_profile_enable(int on);
 int rollattn_profile_read(float *ms_out, int cap);
 

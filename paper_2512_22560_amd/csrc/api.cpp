@@ -26,7 +26,6 @@ bool g_profile = false;
 struct EventPair {
   hipEvent_t a, b;
 };
-std::vector<EventPair> g_events;
 constexpr size_t kMaxEvents = 1024;
 
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -60,24 +59,28 @@ int check_desc(const rollattn_desc* d, bool need_scales = true) {
   return ROLLATTN_OK;
 }
 
+// Timing events are created when profiling is switched on, never inside an attention call: a call only
+// records a pair from the pool, and records nothing on a stream that is being captured into a graph
+// (events recorded during capture cannot be read back).
+std::vector<EventPair> g_pool;
+size_t g_used = 0;
+
 struct ProfileScope {
   hipStream_t s;
   bool on = false;
   EventPair ev{};
   explicit ProfileScope(hipStream_t stream) : s(stream) {
     std::lock_guard<std::mutex> lk(g_mu);
-    if (g_profile && g_events.size() < kMaxEvents) {
-      if (hipEventCreate(&ev.a) == hipSuccess && hipEventCreate(&ev.b) == hipSuccess) {
-        on = true;
-        (void)hipEventRecord(ev.a, s);
-      }
-    }
+    if (!g_profile || g_used >= g_pool.size()) return;
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess || st != hipStreamCaptureStatusNone) return;
+    ev = g_pool[g_used++];
+    on = true;
+    (void)hipEventRecord(ev.a, s);
   }
   void stop() {
     if (!on) return;
     (void)hipEventRecord(ev.b, s);
-    std::lock_guard<std::mutex> lk(g_mu);
-    g_events.push_back(ev);
     on = false;
   }
 };
@@ -270,6 +273,21 @@ int32_t rollattn_plan_workers(const rollattn_desc* desc) {
   return decode_layout(*desc).workers;
 }
 
+// Shape limits of the decode path and of the append path beyond the descriptor checks; the entry points that
+// chain several launches check both before the first one.
+static int decode_limits(const rollattn_desc& d) {
+  const WorkspaceLayout w = decode_layout(d);
+  // the block sequence is indexed with 32-bit integers
+  if ((int64_t)d.batch * w.rows_per_b * ((int64_t)d.max_pages_per_seq / 2 + 1) > INT32_MAX) return ROLLATTN_ESHAPE;
+  // a worker's start record packs the row index into 11 bits and the block index into 20
+  if (w.rows_per_b > 2047 || d.max_pages_per_seq / 2 + 1 > (1 << 20)) return ROLLATTN_ESHAPE;
+  return ROLLATTN_OK;
+}
+static int append_limits(const rollattn_desc& d) {
+  if (d.q_dtype != ROLLATTN_F32 && d.num_q_heads / d.num_kv_heads > kAppendTileRows) return ROLLATTN_ESHAPE;
+  return ROLLATTN_OK;
+}
+
 // attn_decode proper; lse (optional, device [B][Hq]) receives log2 of every row's softmax denominator.
 // q_lens / q_offsets (both or neither): the mixed step, see DecodeArgs.
 static int decode_impl(const rollattn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
@@ -285,10 +303,8 @@ static int decode_impl(const rollattn_desc* desc, const void* q, const void* k_p
     return ROLLATTN_EALIGN;
   const WorkspaceLayout w = decode_layout(*desc);
   if (workspace_bytes < w.total) return ROLLATTN_EWORKSPACE;
-  // the block sequence is indexed with 32-bit integers
-  if ((int64_t)desc->batch * w.rows_per_b * ((int64_t)desc->max_pages_per_seq / 2 + 1) > INT32_MAX) return ROLLATTN_ESHAPE;
-  // a worker's start record packs the row index into 11 bits and the block index into 20
-  if (w.rows_per_b > 2047 || desc->max_pages_per_seq / 2 + 1 > (1 << 20)) return ROLLATTN_ESHAPE;
+  rc = decode_limits(*desc);
+  if (rc) return rc;
 
   hipStream_t s = (hipStream_t)hip_stream;
   char* base = (char*)workspace;
@@ -391,7 +407,8 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
   int rc = check_desc(desc);
   if (rc) return rc;
   if (total_q < 0 || max_q_len < 0) return ROLLATTN_EINVAL;
-  if (desc->q_dtype != ROLLATTN_F32 && desc->num_q_heads / desc->num_kv_heads > kAppendTileRows) return ROLLATTN_ESHAPE;
+  rc = append_limits(*desc);
+  if (rc) return rc;
   if (desc->batch == 0 || total_q == 0) return ROLLATTN_OK;
   if (!q_chunk || !q_lens || !q_offsets || !k_pages || !v_pages || !page_table || !ctx_lens || !out || !workspace)
     return ROLLATTN_EINVAL;
@@ -518,8 +535,13 @@ int attn_step(const rollattn_desc* desc, const void* q, const int32_t* q_lens, c
     return append_impl(desc, q, q_lens, q_offsets, total_q, max_q_len, k_pages, v_pages, page_table, ctx_lens, out,
                        workspace, workspace_bytes, hip_stream, desc->max_pages_per_seq, false, nullptr);
   }
-  if (!q_lens || !q_offsets) return ROLLATTN_EINVAL;
-  if (!aligned16(q_lens) || !aligned16(q_offsets)) return ROLLATTN_EALIGN;
+  if (!q || !q_lens || !q_offsets || !k_pages || !v_pages || !page_table || !ctx_lens || !out) return ROLLATTN_EINVAL;
+  if (!aligned16(q) || !aligned16(q_lens) || !aligned16(q_offsets) || !aligned16(k_pages) || !aligned16(v_pages) ||
+      !aligned16(page_table) || !aligned16(ctx_lens) || !aligned16(out))
+    return ROLLATTN_EALIGN;
+  rc = append_limits(*desc);                       // everything either half could object to, before the first launch
+  if (!rc) rc = decode_limits(*desc);
+  if (rc) return rc;
   const size_t dec_bytes = align256(decode_layout(*desc).total);
   // the long tiles of the chunks first, then the decode rows and their merge; all on one stream, disjoint output rows
   rc = append_impl(desc, q, q_lens, q_offsets, total_q, max_q_len, k_pages, v_pages, page_table, ctx_lens, out,
@@ -588,6 +610,9 @@ int attn_decode_shared(const rollattn_desc* desc, const void* q, const void* k_p
     return ROLLATTN_EALIGN;
   const SharedLayout L = shared_layout(*desc, group_size);
   if (workspace_bytes < L.total) return ROLLATTN_EWORKSPACE;
+  rc = append_limits(L.grp);                       // everything either half could object to, before the first launch
+  if (!rc) rc = decode_limits(*desc);
+  if (rc) return rc;
   hipStream_t s = (hipStream_t)hip_stream;
   char* base = (char*)workspace;
   int32_t* grp_ctx = (int32_t*)(base + L.grp_ctx);
@@ -673,6 +698,24 @@ int rollattn_debug_check_inputs(const rollattn_desc* desc, const int32_t* page_t
 
 int rollattn_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_mu);
+  if (on && g_pool.empty()) {
+    g_pool.reserve(kMaxEvents);
+    for (size_t i = 0; i < kMaxEvents; ++i) {
+      EventPair ev{};
+      hipError_t e = hipEventCreate(&ev.a);
+      if (e == hipSuccess) {
+        e = hipEventCreate(&ev.b);
+        if (e != hipSuccess) (void)hipEventDestroy(ev.a);
+      }
+      if (e != hipSuccess) {
+        g_hip_error = hipGetErrorString(e);
+        for (auto& p : g_pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+        g_pool.clear();
+        return ROLLATTN_EHIP;
+      }
+      g_pool.push_back(ev);
+    }
+  }
   g_profile = on != 0;
   return ROLLATTN_OK;
 }
@@ -681,15 +724,14 @@ int rollattn_profile_read(float* ms_out, int cap) {
   std::vector<EventPair> evs;
   {
     std::lock_guard<std::mutex> lk(g_mu);
-    evs.swap(g_events);
+    evs.assign(g_pool.begin(), g_pool.begin() + g_used);
+    g_used = 0;
   }
   int n = 0;
   for (auto& ev : evs) {
     float ms = 0.f;
     hipError_t e = hipEventSynchronize(ev.b);
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
-    (void)hipEventDestroy(ev.a);
-    (void)hipEventDestroy(ev.b);
     if (e == hipSuccess && ms_out && n < cap) ms_out[n++] = ms;
   }
   return n;

@@ -293,12 +293,14 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     *(uintx4*)(tile + (off ^ 16)) = hi;
   };
   // -- direct path (bf16): HBM -> LDS without a register stop.  Lane l's 16 bytes land at
-  // M0 + 16 l.  The compiler does not see these loads: completion is awaited by count below, and
-  // nothing else in the loop uses the vector-memory counter.  M0 is not live across statements in
-  // compiler-generated code, so it is simply overwritten.
+  // M0 + 16 l.  The compiler does not see these loads as loads: completion is awaited by count
+  // below, which is sound only as long as nothing else in the loop uses the vector-memory counter,
+  // register spills to scratch memory included (the build checks that this kernel has none).  M0 is
+  // a reserved register for this compiler (it refuses it in a clobber list) and is never live
+  // across statements in the code it generates, so it is simply overwritten.
   auto dma = [&](const TileAddr& t, unsigned char* lds_dst) __attribute__((always_inline)) {
     const unsigned int m0 = __builtin_amdgcn_readfirstlane((unsigned int)(uintptr_t)lds_dst);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(t.off), "s"(t.base));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(t.off), "s"(t.base) : "memory");
   };
 #define DMA_WAIT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n))
 

@@ -41,6 +41,13 @@ ATTENTION = ("attention.py", "tests/test_oracle_pins.py", [
     ("merge of ranges: denominator without the reference", "lse = np.where(tot > 0, safe + np.log2(tot), -np.inf)",
      "lse = np.where(tot > 0, np.log2(tot), -np.inf)"),
     ("merge of ranges: plain average", "(w1[..., None] * o1 + w2[..., None] * o2) / tot[..., None]", "(o1 + o2) / 2"),
+    ("tile list: shortest context first", "order.sort(key=lambda b: (-ctx[b], b))", "order.sort(key=lambda b: (ctx[b], b))"),
+    ("tile list: a chunk's first tile first", "for start in reversed(starts):", "for start in starts:"),
+    ("tile list: last tile takes a full tile's rows", "tiles.append((b, start, min(tile_tokens, q[b] - start)))",
+     "tiles.append((b, start, tile_tokens))"),
+    ("tile list: one-token chunks kept in a mixed step", "if skip_unit_chunks and q[b] == 1:", "if False:"),
+    ("tile list: ties by higher index", "order.sort(key=lambda b: (-ctx[b], b))", "order.sort(key=lambda b: (-ctx[b], -b))"),
+    ("partition: runs one block short", "per = max(1, -(-total // workers))", "per = max(1, total // workers)"),
 ])
 
 KV_WRITE = ("kv_write.py", "tests/test_kv_write_pins.py", [

@@ -99,7 +99,6 @@ WorkspaceLayout decode_layout(const rollattn_desc& d) {
   w.header = off;      off += align256(sizeof(int32_t) * kPlanWords);
   w.prefix = off;      off += align256(sizeof(int32_t) * ((size_t)d.batch + 1));
   w.wstart = off;      off += align256(sizeof(int32_t) * 4 * (size_t)w.workers);
-  w.tile_q0 = off;
   w.partial_ml = off;  off += align256(sizeof(float) * 2 * (size_t)w.workers * w.head_tile * 2);
   w.partial_o = off;   off += align256(sizeof(float) * 2 * (size_t)w.workers * w.head_tile * d.head_dim);
   w.total = off;
@@ -113,8 +112,7 @@ WorkspaceLayout append_layout(const rollattn_desc& d, int32_t total_q) {
   w.workers = (int32_t)std::min<int64_t>((int64_t)total_q / tile_tokens + d.batch + 1, INT32_MAX);
   size_t off = 0;
   w.header = off;      off += align256(sizeof(int32_t) * kPlanWords);
-  w.wstart = off;      off += align256(sizeof(int32_t) * (size_t)w.workers);
-  w.tile_q0 = off;     off += align256(sizeof(int32_t) * (size_t)w.workers);
+  w.wstart = off;      off += align256(sizeof(int32_t) * kTileRecWords * (size_t)w.workers);
   w.prefix = off;
   w.partial_ml = off;
   w.partial_o = off;
@@ -192,16 +190,15 @@ int rollattn_debug_read_append_plan(const rollattn_desc* desc, const void* works
   if (e != hipSuccess) return fail_hip(e);
   const char* base = (const char*)workspace;
   int32_t header[kPlanWords];
-  std::vector<int32_t> tb((size_t)w.workers), tq((size_t)w.workers);
+  std::vector<int32_t> rec((size_t)w.workers * kTileRecWords);
   e = hipMemcpy(header, base + w.header, sizeof(header), hipMemcpyDeviceToHost);
-  if (e == hipSuccess) e = hipMemcpy(tb.data(), base + w.wstart, sizeof(int32_t) * tb.size(), hipMemcpyDeviceToHost);
-  if (e == hipSuccess) e = hipMemcpy(tq.data(), base + w.tile_q0, sizeof(int32_t) * tq.size(), hipMemcpyDeviceToHost);
+  if (e == hipSuccess) e = hipMemcpy(rec.data(), base + w.wstart, sizeof(int32_t) * rec.size(), hipMemcpyDeviceToHost);
   if (e != hipSuccess) return fail_hip(e);
   const int32_t n = std::max(0, std::min(header[kPlanTiles], w.workers));
   *n_tiles_out = n;
   for (int32_t i = 0; i < n; ++i) {
-    tiles_out[2 * i] = tb[i];
-    tiles_out[2 * i + 1] = tq[i];
+    tiles_out[2 * i] = rec[(size_t)i * kTileRecWords];
+    tiles_out[2 * i + 1] = rec[(size_t)i * kTileRecWords + 1];
   }
   return ROLLATTN_OK;
 }
@@ -363,8 +360,8 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
   a.q = q_chunk; a.k_pages = k_pages; a.v_pages = v_pages; a.page_table = page_table; a.ctx_lens = ctx_lens;
   a.q_lens = q_lens; a.q_offsets = q_offsets; a.out = out; a.k_scale = desc->k_scale; a.v_scale = desc->v_scale;
   a.header = (int32_t*)(base + w.header);
-  a.tile_b = (const int32_t*)(base + w.wstart);
-  a.tile_q0 = (const int32_t*)(base + w.tile_q0);
+  a.tile_rec = (const int32_t*)(base + w.wstart);
+  a.tile_cap = w.workers;
   a.batch = desc->batch; a.hq = desc->num_q_heads; a.hkv = desc->num_kv_heads;
   a.group = desc->num_q_heads / desc->num_kv_heads; a.max_pages = table_stride;
   a.tile_tokens = std::max(1, kAppendTileRows / a.group);
@@ -383,8 +380,8 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
     if (e != hipSuccess) return fail_hip(e);
     return ROLLATTN_OK;
   }
-  e = launch_plan_append(q_lens, ctx_lens, desc->batch, a.tile_tokens, w.workers, skip_unit_chunks, a.header,
-                         (int32_t*)(base + w.wstart), (int32_t*)(base + w.tile_q0), s);
+  e = launch_plan_append(q_lens, q_offsets, ctx_lens, desc->batch, a.tile_tokens, w.workers, skip_unit_chunks, a.header,
+                         (int32_t*)(base + w.wstart), s);
   if (e != hipSuccess) return fail_hip(e);
   {
     ProfileScope prof(s);

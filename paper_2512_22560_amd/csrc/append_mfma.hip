@@ -130,24 +130,24 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   // own; tiles of one trajectory and KV head walk the same K/V stream and should share one L2.  With the
   // plain order (head fastest) that holds when the head count is a multiple of 8: XCD x then only ever sees
   // heads x, x + 8, ...  With 1, 2 or 4 KV heads a head's tiles would be dealt to 8, 4 or 2 XCDs and each of
-  // them would fetch the whole stream; there the 8 / Hkv XCDs that serve a head take turns by runs of up to
-  // 32 consecutive tiles of the list (one per CU of an XCD; the list keeps a trajectory's tiles together).
+  // them would fetch the whole stream; there the 8 / Hkv XCDs that serve a head take turns by runs of
+  // kAppendXcdRun consecutive tiles of the list (the list keeps a trajectory's tiles together).
   int tile, g;
   if (hkv < kXcds && kXcds % hkv == 0) {
     const int x = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
     const int parts = kXcds / hkv;
-    const int run = min(kAppendXcdRun, (n_tiles + parts - 1) / parts);
     g = x % hkv;
-    tile = run > 0 ? (slot / run) * (parts * run) + (x / hkv) * run + slot % run : n_tiles;
+    tile = (slot / kAppendXcdRun) * (parts * kAppendXcdRun) + (x / hkv) * kAppendXcdRun + slot % kAppendXcdRun;
   } else {
     tile = blockIdx.x / hkv;
     g = blockIdx.x - tile * hkv;
   }
+  // The tile's record does not wait for the tile count (the index is clamped to the list's capacity): both loads
+  // leave together, and everything else the workgroup needs to start hangs off the record alone.
+  typedef const __attribute__((address_space(4))) int32_t* const_rec_p;
+  const const_rec_p rec = (const_rec_p)(a.tile_rec + (size_t)min(tile, a.tile_cap - 1) * kTileRecWords);
+  const int b = rec[0], q0 = rec[1], n_b = rec[2], ctx = rec[3], q_off = rec[4];
   if (tile >= n_tiles) return;
-  const int b = a.tile_b[tile];
-  const int q0 = a.tile_q0[tile];
-  const int n_b = a.q_lens[b];
-  const int ctx = a.ctx_lens[b];
   const int tokens_here = min(tile_tokens, n_b - q0);
   const int rows_here = tokens_here * group;
   // Causal mode: row i of the chunk sits at position L_b - n_b + i and sees tokens up to itself.
@@ -179,26 +179,22 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 
   if (n_blocks <= 0) {                                   // nothing to attend to (non-causal mode with L_b = 0): zero rows
     if (row_ok) {
-      __bf16* orow = (__bf16*)a.out + ((size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head) * D;
+      __bf16* orow = (__bf16*)a.out + ((size_t)(q_off + q0 + tok_in_tile) * a.hq + head) * D;
 #pragma unroll
       for (int d0 = h2 * (D / 2); d0 < (h2 + 1) * (D / 2); d0 += 4) *(bf16x4*)(orow + d0) = bf16x4{0, 0, 0, 0};
-      if (a.lse && h2 == 0) a.lse[(size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head] = -INFINITY;
+      if (a.lse && h2 == 0) a.lse[(size_t)(q_off + q0 + tok_in_tile) * a.hq + head] = -INFINITY;
     }
     return;
   }
 
   bf16x8 qop[kKK];
   {
-    const __bf16* qrow = (const __bf16*)a.q + ((size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head) * D;
+    const __bf16* qrow = (const __bf16*)a.q + ((size_t)(q_off + q0 + tok_in_tile) * a.hq + head) * D;
 #pragma unroll
     for (int kk = 0; kk < kKK; ++kk) {
       bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
       if (row_ok) v = *(const bf16x8*)(qrow + kk * 16 + h2 * 8);
-      if constexpr (!FP8) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = (__bf16)((float)v[e] * a.scale_log2);
-      }
-      qop[kk] = v;
+      qop[kk] = v;                                 // bf16 pools: scaled further down, once the first tiles are on their way
     }
   }
 
@@ -610,6 +606,12 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
           dma(tile_addr(a.k_pages, 0, u0 + 1, tile_off_of(hh[u0 + 1][j]), j), k_lds[0] + (u0 + 1) * kTileBytes + wave * 1024 + j * kThreads * 16);
           dma(tile_addr(a.v_pages, 1, u0, tile_off_of(hh[u0][j]), j), v_lds[0] + u0 * kTileBytes + wave * 1024 + j * kThreads * 16);
         }
+      // the query rows have been under way since the top of the kernel; their scaling (bf16 pools: the
+      // scores then leave the matrix core as exponents) waits for them here, behind the tile loads
+#pragma unroll
+      for (int kk = 0; kk < kKK; ++kk)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qop[kk][e] = (__bf16)((float)qop[kk][e] * a.scale_log2);
       DMA_WAIT((kLead - 1) * 2 * kLoads);            // K block 0 and unit 0 have landed (unit 0 is read early, one barrier from now)
     }
     PHASE_END();
@@ -635,19 +637,22 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
       constexpr int slot = decltype(slot_c)::value;
 #pragma unroll
       for (int j = 0; j < kLoads; ++j) {
-        if (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens) {
+        // (units past the tile's last block are not loaded: what the registers then hold is widened into tiles nobody reads)
+        if (u <= last_blk && (kAllThreadsLoad || (j * kThreads + tid) / kSrcChunks < kBlockTokens)) {
           const TileAddr ka = tile_addr(a.k_pages, 0, u + 1, toff[0][j], j), va = tile_addr(a.v_pages, 1, u, toff[1][j], j);
           kreg[slot][j] = *(const uintx4*)(ka.base + ka.off);
           vreg[slot][j] = *(const uintx4*)(va.base + va.off);
         }
       }
-    } else {
+    } else if (u <= last_blk) {
 #pragma unroll
       for (int j = 0; j < kLoads; ++j) {
         dma(tile_addr(a.k_pages, 0, u + 1, toff[0][j], j), k_lds[0] + ko[kRing - 1] + wave * 1024 + j * kThreads * 16);
         dma(tile_addr(a.v_pages, 1, u, toff[1][j], j), v_lds[0] + ko[kRing - 2] + wave * 1024 + j * kThreads * 16);
       }
       DMA_WAIT(2 * kLoads);                          // everything but the unit just started has landed
+    } else {
+      DMA_WAIT(0);                                   // past the tile's last block nothing is started: the units still on their way are real ones
     }
   };
   // ... and, FP8 only, the widening of unit i (K block i + 1, V block i) from registers into LDS during the
@@ -755,9 +760,9 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   l_run = xor32_add(l_run);
   if (row_ok) {
     // log2 of the row's softmax denominator, for callers that merge this result with another range's
-    if (a.lse && h2 == 0) a.lse[(size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head] = m_run + __builtin_amdgcn_logf(l_run);
+    if (a.lse && h2 == 0) a.lse[(size_t)(q_off + q0 + tok_in_tile) * a.hq + head] = m_run + __builtin_amdgcn_logf(l_run);
     const float inv = 1.f / l_run;
-    __bf16* orow = (__bf16*)a.out + ((size_t)(a.q_offsets[b] + q0 + tok_in_tile) * a.hq + head) * D;
+    __bf16* orow = (__bf16*)a.out + ((size_t)(q_off + q0 + tok_in_tile) * a.hq + head) * D;
 #pragma unroll
     for (int dt = 0; dt < kDT; ++dt) {
 #pragma unroll

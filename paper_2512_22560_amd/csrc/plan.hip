@@ -105,9 +105,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
 // tile first.
 constexpr int kRankBatch = 4096;
 __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
-    const int32_t* __restrict__ q_lens, const int32_t* __restrict__ ctx_lens, int32_t batch, int32_t tile_tokens,
-    int32_t cap, bool skip_unit_chunks, int32_t* __restrict__ header, int32_t* __restrict__ tile_b,
-    int32_t* __restrict__ tile_q0) {
+    const int32_t* __restrict__ q_lens, const int32_t* __restrict__ q_offsets, const int32_t* __restrict__ ctx_lens,
+    int32_t batch, int32_t tile_tokens, int32_t cap, bool skip_unit_chunks, int32_t* __restrict__ header,
+    int32_t* __restrict__ tile_rec) {
   __shared__ int wave_tot[kPlanThreads / 64];
   __shared__ int len_s[kRankBatch];
   __shared__ int order_s[kRankBatch];
@@ -138,10 +138,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
     }
     int tile_total;
     const int first = running + block_exclusive_scan(count, wave_tot, &tile_total);
+    // One 32-byte record per tile with everything the tile's workgroup needs to start, so that it gets there with
+    // one dependent load instead of a chain of them: (b, first row, n_b, L_b, q_offsets[b]).
     for (int s = 0; s < count; ++s) {
       if (first + s < cap) {
-        tile_b[first + s] = b;
-        tile_q0[first + s] = (count - 1 - s) * tile_tokens;   // a chunk's last tile sees the most context
+        int4* rec = (int4*)(tile_rec + (size_t)(first + s) * kTileRecWords);
+        rec[0] = make_int4(b, (count - 1 - s) * tile_tokens, q_lens[b], ctx_lens[b]);   // a chunk's last tile sees the most context
+        rec[1] = make_int4(q_offsets[b], 0, 0, 0);
       }
     }
     running += tile_total;
@@ -158,11 +161,11 @@ hipError_t launch_plan_decode(const int32_t* ctx_lens, const int32_t* q_lens, in
   return hipGetLastError();
 }
 
-hipError_t launch_plan_append(const int32_t* q_lens, const int32_t* ctx_lens, int32_t batch, int32_t tile_tokens,
-                              int32_t cap, bool skip_unit_chunks, int32_t* header, int32_t* tile_b, int32_t* tile_q0,
+hipError_t launch_plan_append(const int32_t* q_lens, const int32_t* q_offsets, const int32_t* ctx_lens, int32_t batch,
+                              int32_t tile_tokens, int32_t cap, bool skip_unit_chunks, int32_t* header, int32_t* tile_rec,
                               hipStream_t s) {
-  hipLaunchKernelGGL(plan_append_kernel, dim3(1), dim3(kPlanThreads), 0, s, q_lens, ctx_lens, batch, tile_tokens, cap,
-                     skip_unit_chunks, header, tile_b, tile_q0);
+  hipLaunchKernelGGL(plan_append_kernel, dim3(1), dim3(kPlanThreads), 0, s, q_lens, q_offsets, ctx_lens, batch, tile_tokens,
+                     cap, skip_unit_chunks, header, tile_rec);
   return hipGetLastError();
 }
 

@@ -18,6 +18,7 @@ constexpr int kF32DecodeWgs = 4 * kNumCUs;    // one workgroup-worker each
 constexpr int kF32HeadTile = 4;         // query heads per float32 decode row
 constexpr int kAppendTileRows = 256;    // query rows (token, head-in-group pairs) per append workgroup
 constexpr int kXcds = 8;                // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
+constexpr int kTileRecWords = 8;       // append: int32 per tile record (32 bytes: one scalar load)
 constexpr int kAppendXcdRun = 16;       // append: consecutive tiles of the list that one XCD takes in a row (one per CU)
 
 // Header words of the plan, at the start of the workspace.
@@ -30,8 +31,7 @@ struct WorkspaceLayout {
   int32_t rows_per_b;     // decode: rows per trajectory = Hkv * ceil(G / head_tile)
   size_t header;          // int32[kPlanWords]
   size_t prefix;          // decode: int32[B + 1] exclusive scan of per-trajectory block counts
-  size_t wstart;          // decode: int32[W][4] first (b, row, block) of every worker; append: tile list
-  size_t tile_q0;         // append: int32[cap]
+  size_t wstart;          // decode: int32[W][4] first (b, row, block) of every worker; append: int32[cap][8] tile records
   size_t partial_ml;      // float[2 W][head_tile][2]   (max in log2 units, sum)
   size_t partial_o;       // float[2 W][head_tile][D]   un-normalised
   size_t total;
@@ -76,8 +76,8 @@ struct AppendArgs {
   const float* k_scale;
   const float* v_scale;
   int32_t* header;
-  const int32_t* tile_b;
-  const int32_t* tile_q0;
+  const int32_t* tile_rec;   // [tile_cap][kTileRecWords]: (b, first row of the tile in its chunk, n_b, L_b, q_offsets[b], 0, 0, 0)
+  int32_t tile_cap;
   int32_t batch, hq, hkv, group, max_pages, tile_tokens, total_q;
   float scale_log2;
   float* lse;           // optional [total_q][Hq], as in DecodeArgs
@@ -87,8 +87,8 @@ struct AppendArgs {
 // Launchers (defined in the .hip files).  Each returns the hipError_t of its launch.
 hipError_t launch_plan_decode(const int32_t* ctx_lens, const int32_t* q_lens, int32_t batch, int32_t rows_per_b,
                               int32_t workers, int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s);
-hipError_t launch_plan_append(const int32_t* q_lens, const int32_t* ctx_lens, int32_t batch, int32_t tile_tokens,
-                              int32_t cap, bool skip_unit_chunks, int32_t* header, int32_t* tile_b, int32_t* tile_q0,
+hipError_t launch_plan_append(const int32_t* q_lens, const int32_t* q_offsets, const int32_t* ctx_lens, int32_t batch,
+                              int32_t tile_tokens, int32_t cap, bool skip_unit_chunks, int32_t* header, int32_t* tile_rec,
                               hipStream_t s);
 hipError_t launch_decode_f32(const DecodeArgs& a, int head_dim, int grid, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeArgs& a, int head_dim, bool fp8, int grid, hipStream_t s);

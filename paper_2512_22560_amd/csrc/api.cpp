@@ -365,6 +365,11 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
   a.batch = desc->batch; a.hq = desc->num_q_heads; a.hkv = desc->num_kv_heads;
   a.group = desc->num_q_heads / desc->num_kv_heads; a.max_pages = table_stride;
   a.tile_tokens = std::max(1, kAppendTileRows / a.group);
+  // No chunk longer than half a tile (a few new tokens per trajectory; the members of a group in attn_decode_shared):
+  // half tiles, whose blocks the two waves of a SIMD share (FP8 pools)
+  const bool half_tiles = desc->kv_dtype == ROLLATTN_FP8_E4M3 && desc->q_dtype != ROLLATTN_F32 &&
+                          (int64_t)max_q_len * a.group <= kAppendTileRows / 2;
+  if (half_tiles) a.tile_tokens = std::max(1, kAppendTileRows / 2 / a.group);
   a.total_q = total_q;
   a.scale_log2 = desc->sm_scale * 1.4426950408889634f;
   a.lse = lse;
@@ -393,7 +398,7 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
       grid64 = kXcds * (((int64_t)w.workers + parts - 1) / parts + kAppendXcdRun);
     }
     const int grid = (int)std::min<int64_t>(grid64, INT32_MAX);
-    e = launch_append_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, grid, s);
+    e = launch_append_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, half_tiles, grid, s);
     prof.stop();
   }
   if (e != hipSuccess) return fail_hip(e);

@@ -51,6 +51,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
@@ -97,7 +98,11 @@ __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-template <int D, bool FP8>
+// HALF: for tiles of at most 128 rows.  With the plain layout such a tile keeps only the leading four waves busy
+// and the two pipelines of a SIMD take turns.  Here waves w and w + 4 both own rows 32 (w % 4) .. and split every
+// block between them: the leading wave takes its first 32 tokens, the trailing wave the other 32, each with a
+// running reference, sum and accumulator of its own, merged through LDS when the tile ends.
+template <int D, bool FP8, bool HALF>
 __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs a) {
   constexpr int kRowBytes = D * 2;                 // bf16 rows in LDS
   constexpr int kChunks = kRowBytes / 16;          // 16-byte chunks per LDS row
@@ -115,6 +120,10 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   constexpr int kRing = FP8 ? 2 : 4;
   __shared__ __attribute__((aligned(1024))) unsigned char k_lds[kRing][kTileBytes];
   __shared__ __attribute__((aligned(1024))) unsigned char v_lds[kRing][kTileBytes];
+  // HALF: where the trailing waves leave their result for the leading ones: per wave pair the accumulators
+  // [D / 32][4][64 lanes] as 16-byte quads, then reference and sum
+  constexpr int kMergeFloats = HALF ? (D / 32) * 16 * 64 + 2 * 64 : 1;
+  __shared__ __attribute__((aligned(16))) float merge_s[HALF ? kWaves / 2 : 1][kMergeFloats];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -167,15 +176,17 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   const size_t tile_stride = (size_t)kPageSize * kSrcRowBytes;
 
   // ---- this lane's query row
-  const int row = wave * kRowsPerWave + n32;
+  const int grp = wave >> 2;   // 0: leading half of the workgroup, 1: the half that runs one phase behind (waves w and w + 4 share a SIMD)
+  const int row_wave = HALF ? (wave & 3) : wave;         // which 32 rows of the tile this wave owns
+  const int sub0 = HALF ? grp : 0;                       // HALF: which 32 tokens of every block
+  const int row = row_wave * kRowsPerWave + n32;
   const bool row_ok = row < rows_here;
   const int tok_in_tile = row / group;
   const int head = g * group + (row - tok_in_tile * group);
   const int my_pos = row_ok ? (causal ? pos0 + tok_in_tile : pos0) : -1;   // last visible token of this row
   // blocks that end at or before this position are fully visible to every row of the wave
-  const bool wave_active = wave * kRowsPerWave < rows_here;
-  const int wave_min_pos = wave_active ? (causal ? pos0 + (wave * kRowsPerWave) / group : pos0) : -1;
-  const int grp = wave >> 2;   // 0: leading half of the workgroup, 1: the half that runs one phase behind (waves w and w + 4 share a SIMD)
+  const bool wave_active = row_wave * kRowsPerWave < rows_here;
+  const int wave_min_pos = wave_active ? (causal ? pos0 + (row_wave * kRowsPerWave) / group : pos0) : -1;
 
   if (n_blocks <= 0) {                                   // nothing to attend to (non-causal mode with L_b = 0): zero rows
     if (row_ok) {
@@ -300,18 +311,20 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   };
 #define DMA_WAIT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n))
 
-  // FP8: scales of the four pages of a block (scalar loads), folded with the softmax scale; the page
-  // ids behind them are fetched one vector phase before the scales, the scales one vector phase before use
-  float ksc_cur[4], lvs_cur[4], ivs_cur[4];   // per page of the block: K scale times softmax scale, log2 of the V scale, its reciprocal
-  int spid[kPagesPerBlock];
+  // FP8: scales of the pages of a block that this wave's tokens lie in (all four; HALF: two), by scalar loads,
+  // folded with the softmax scale; the page ids behind them are fetched one vector phase before the scales,
+  // the scales one vector phase before use
+  constexpr int kPg = HALF ? kPagesPerBlock / 2 : kPagesPerBlock;
+  float ksc_cur[kPg], lvs_cur[kPg], ivs_cur[kPg];   // per page: K scale times softmax scale, log2 of the V scale, its reciprocal
+  int spid[kPg];
   auto fetch_spids = [&](int blk) __attribute__((always_inline)) {
 #pragma unroll
-    for (int p = 0; p < kPagesPerBlock; ++p)
-      spid[p] = FP8 ? table[min(min(blk, last_blk) * kPagesPerBlock + p, live_pages - 1)] : 0;
+    for (int p = 0; p < kPg; ++p)
+      spid[p] = FP8 ? table[min(min(blk, last_blk) * kPagesPerBlock + sub0 * kPg + p, live_pages - 1)] : 0;
   };
   auto load_scales = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int p = 0; p < kPagesPerBlock; ++p) {
+    for (int p = 0; p < kPg; ++p) {
       if (FP8) {
         const float vs = v_scale_c[spid[p]];
         ksc_cur[p] = k_scale_c[spid[p]] * a.scale_log2;
@@ -341,15 +354,18 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
                  (((dt * 4 + ((lane >> 4) & 1) * 2 + ((j & 3) >> 1)) ^ ((tv & 3) << 2)) & (kChunks - 1)) * 16 + (j & 1) * 8;
   }
 
-  constexpr int kSubs = kBlockTokens / 32;
+  constexpr int kSubs = HALF ? 1 : kBlockTokens / 32;   // 32-token sub-blocks of a block that this wave works on
+  constexpr int kPvSteps = 8 * kSubs, kSteps = 16 * kSubs;
+  const int sub_bytes = sub0 * 32 * kRowBytes;           // HALF: where this wave's tokens start in a K or V tile
   floatx16 s[kSubs];        // scores of the block between its two phases
   bf16x8 pop[kSubs][2];     // its probabilities, as B operands of the second product
 
-  // ---- matrix phase: up to 32 MFMA steps, O^T += V^T P^T for the previous block (steps 0-15, V buffer
-  // at vbo) and S^T = K Q^T for this one (steps 16-31, K buffer at kbo).  Every step needs one 32x16 operand
-  // from LDS; the reads run kAhead steps in front of the MFMAs that consume them, because during
-  // this phase no second wave hides the LDS latency.  After the step at schedule position pos the
-  // caller's piece(pos) runs: the FP8 path threads its LDS writes between the MFMAs there.
+  // ---- matrix phase: up to kSteps (32; HALF: 16) MFMA steps, O^T += V^T P^T for the previous block (the
+  // first kPvSteps, V buffer at vbo) and S^T = K Q^T for this one (the others, K buffer at kbo).  Every step
+  // needs one 32x16 operand from LDS; the reads run kAhead steps in front of the MFMAs that consume them,
+  // because during this phase no second wave hides the LDS latency.  The phase has 32 schedule positions
+  // spread evenly over its steps; after a step the caller's piece(pos) runs for the positions that belong to
+  // it: the FP8 path threads its LDS writes between the MFMAs there.
   constexpr int kAhead = 4;
   // bf16 pools: the operands of the first kAhead steps of a phase that starts with the second product are
   // read at the end of the vector phase before it, in front of the barrier (the V tile they come from was
@@ -371,29 +387,29 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     }
   };
   auto read_early = [&](int vbo) __attribute__((always_inline)) {
-    static_for<kAhead>([&](auto t_c) __attribute__((always_inline)) { read_v_operand(v_lds[0] + vbo, t_c, early[decltype(t_c)::value]); });
+    static_for<kAhead>([&](auto t_c) __attribute__((always_inline)) { read_v_operand(v_lds[0] + vbo + sub_bytes, t_c, early[decltype(t_c)::value]); });
   };
   auto matrix_phase = [&](auto first_c, auto last_c, int kbo, int vbo, auto&& piece) __attribute__((always_inline)) {
     constexpr int T0 = decltype(first_c)::value, T1 = decltype(last_c)::value;
-    const unsigned char* kbuf = k_lds[0] + kbo;    // byte offsets of the ring slots
-    const unsigned char* vbuf = v_lds[0] + vbo;
-    bf16x8 ops[32];
+    const unsigned char* kbuf = k_lds[0] + kbo + sub_bytes;    // byte offsets of the ring slots
+    const unsigned char* vbuf = v_lds[0] + vbo + sub_bytes;
+    bf16x8 ops[kSteps];
     auto fetch = [&](auto t_c) __attribute__((always_inline)) {
       constexpr int t = decltype(t_c)::value;
-      if constexpr (t < 16) {
+      if constexpr (t < kPvSteps) {
         read_v_operand(vbuf, t_c, ops[t]);
       } else {
-        constexpr int u = t - 16, kk = u >> 1, sub = u & 1;
+        constexpr int u = t - kPvSteps, kk = u / kSubs, sub = u % kSubs;
         if constexpr (kk < kKK) ops[t] = *(const bf16x8*)(kbuf + sub * 32 * kRowBytes + koff[kk]);
       }
     };
     auto fire = [&](auto t_c) __attribute__((always_inline)) {
       constexpr int t = decltype(t_c)::value;
-      if constexpr (t < 16) {
+      if constexpr (t < kPvSteps) {
         constexpr int sub = t >> 3, ks = (t >> 2) & 1, dt = t & 3;
         if constexpr (dt < kDT) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ops[t], pop[sub][ks], acc[dt], 0, 0, 0);
       } else {
-        constexpr int u = t - 16, kk = u >> 1, sub = u & 1;
+        constexpr int u = t - kPvSteps, kk = u / kSubs, sub = u % kSubs;
         if constexpr (kk < kKK) {
           if constexpr (kk == 0) {
             if constexpr (FP8) {
@@ -415,12 +431,13 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
       else if constexpr (t < T1) fetch(std::integral_constant<int, t>{});
     });
     __builtin_amdgcn_sched_barrier(0);
-    static_for<32>([&](auto t_c) __attribute__((always_inline)) {
+    static_for<kSteps>([&](auto t_c) __attribute__((always_inline)) {
       constexpr int t = decltype(t_c)::value;
       if constexpr (t >= T0 && t < T1) {
         if constexpr (t + kAhead < T1) fetch(std::integral_constant<int, t + kAhead>{});
         fire(t_c);
-        piece(std::integral_constant<int, (t - T0) * 32 / (T1 - T0)>{});
+        constexpr int P0 = (t - T0) * 32 / (T1 - T0), P1 = (t + 1 - T0) * 32 / (T1 - T0);
+        static_for<P1 - P0>([&](auto d_c) __attribute__((always_inline)) { piece(std::integral_constant<int, P0 + decltype(d_c)::value>{}); });
         __builtin_amdgcn_sched_barrier(0);           // the source order of the steps is the schedule
       }
     });
@@ -439,22 +456,23 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   // reference yet, does the wave find the true maxima, move the references there, rescale the
   // accumulators and redo the block's exponentials.  In all other blocks the maximum, a chain of
   // dependent steps across the row, is never computed.
+  static_assert(kPg == 2 * kSubs, "two pages per 32-token sub-block");
   auto softmax = [&](int blk) __attribute__((always_inline)) {
-    float sc[4];
+    float sc[kPg], lvs[kPg], ivs[kPg];                 // this wave's pages: K scale times softmax scale, log2 of the V scale, its reciprocal
     if constexpr (FP8) {
 #pragma unroll
-      for (int p = 0; p < 4; ++p) sc[p] = ksc_cur[p];
+      for (int p = 0; p < kPg; ++p) { sc[p] = ksc_cur[p]; lvs[p] = lvs_cur[p]; ivs[p] = ivs_cur[p]; }
       if (!positive_scale) {                           // rare: scale the scores themselves instead
 #pragma unroll
         for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
           for (int i = 0; i < 16; ++i) s[sub][i] *= sc[sub * 2 + (i >> 3)];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) sc[p] = 1.f;
+        for (int p = 0; p < kPg; ++p) sc[p] = 1.f;
       }
     }
-    const int tok0 = blk * kBlockTokens;
-    if (tok0 + kBlockTokens - 1 > wave_min_pos) {      // causal edge or ragged end inside this block
+    const int tok0 = blk * kBlockTokens + sub0 * 32;     // first token of this wave's share of the block
+    if (tok0 + kSubs * 32 - 1 > wave_min_pos) {        // causal edge or ragged end inside this block
 #pragma unroll
       for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
@@ -467,10 +485,10 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     float p[kSubs][16];
     // exponentials of the block against reference m_old + shift, and this lane's share of the row sums
     auto exponentials = [&](auto first_c, float shift) __attribute__((always_inline)) -> float {
-      float ad[4], psum[4];
+      float ad[kPg], psum[kPg];
       if constexpr (FP8) {
 #pragma unroll
-        for (int pg = 0; pg < 4; ++pg) ad[pg] = lvs_cur[pg] - (m_old + shift);
+        for (int pg = 0; pg < kPg; ++pg) ad[pg] = lvs[pg] - (m_old + shift);
       }
 #pragma unroll
       for (int sub = 0; sub < kSubs; ++sub)
@@ -485,7 +503,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
           if ((i & 7) == 0) psum[pg] = p[sub][i];
           else psum[pg] += p[sub][i];
         }
-      if constexpr (FP8) return (psum[0] * ivs_cur[0] + psum[1] * ivs_cur[1]) + (psum[2] * ivs_cur[2] + psum[3] * ivs_cur[3]);
+      if constexpr (HALF) return FP8 ? psum[0] * ivs[0] + psum[1] * ivs[1] : psum[0] + psum[1];
+      else if constexpr (FP8) return (psum[0] * ivs[0] + psum[1] * ivs[1]) + (psum[2] * ivs[2] + psum[3] * ivs[3]);
       else return (psum[0] + psum[1]) + (psum[2] + psum[3]);
     };
     float lane_sum = exponentials(std::true_type{}, 0.f);
@@ -494,9 +513,9 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     if (__builtin_amdgcn_ballot_w64(bump)) {
       // largest exponent of the block: FP8 page scales and the softmax scale are positive here, so the maximum
       // can be taken on the raw products of each page
-      float pm[4];
+      float pm[kPg];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < kPg; ++q) {
         const int sub = q >> 1, o = (q & 1) * 8;
         float x = fmaxf(fmaxf(s[sub][o], s[sub][o + 1]), s[sub][o + 2]);
         x = fmaxf(fmaxf(x, s[sub][o + 3]), s[sub][o + 4]);
@@ -504,7 +523,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
         pm[q] = fmaxf(x, s[sub][o + 7]);
       }
       float mloc;
-      if constexpr (FP8) mloc = fmaxf(fmaxf(pm[0] * sc[0], pm[1] * sc[1]), fmaxf(pm[2] * sc[2], pm[3] * sc[3]));
+      if constexpr (HALF) mloc = FP8 ? fmaxf(pm[0] * sc[0], pm[1] * sc[1]) : fmaxf(pm[0], pm[1]) + m_old;
+      else if constexpr (FP8) mloc = fmaxf(fmaxf(pm[0] * sc[0], pm[1] * sc[1]), fmaxf(pm[2] * sc[2], pm[3] * sc[3]));
       else mloc = fmaxf(fmaxf(pm[0], pm[1]), fmaxf(pm[2], pm[3])) + m_old;
       const float m_new = fmaxf(m_run, xor32_max(mloc));           // the same in both lanes of a row
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;     // rows that see nothing yet
@@ -560,8 +580,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #define PHASE_END() do { __builtin_amdgcn_sched_barrier(0); BARRIER_RAW(); __builtin_amdgcn_sched_barrier(0); } while (0)
   constexpr std::integral_constant<int, 0> even{};
   constexpr std::integral_constant<int, 1> odd{};
-  constexpr std::integral_constant<int, 16> c16{};
-  constexpr std::integral_constant<int, 32> c32{};
+  constexpr std::integral_constant<int, kPvSteps> c16{};   // first step of the first product
+  constexpr std::integral_constant<int, kSteps> c32{};     // end of the phase
   // Page ids run ahead of the tile loads, so that no load ever waits for an address: U = i + kLead being
   // the unit whose loads a wave starts in its vector phase of block i, toff holds (on entry to that
   // phase) the tile offsets of block U and pid_new the page ids of block U + 1.
@@ -573,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   int ko[kRing];
 #pragma unroll
   for (int d = 0; d < kRing; ++d) ko[d] = d * kTileBytes;
-  unsigned int kraw[4], vraw[4];
+  unsigned int kraw[kPg], vraw[kPg];
   {
     int h0[kLoads], h1[kLoads], h2[kLoads], h3[kLoads];
     fetch_pids(0, h0); fetch_pids(1, h1); fetch_pids(2, h2); fetch_pids(3, h3);
@@ -673,14 +693,20 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   auto scalar_issue = [&](int i) __attribute__((always_inline)) {
     fetch_pids(i + kLead + 2, pid_new);
     if constexpr (FP8) {
-      // scales of block i + 1: eight loads in one statement, so that each keeps a register of its
+      // scales of block i + 1: all loads in one statement, so that each keeps a register of its
       // own (the compiler would recycle one register and wait after every load)
+      if constexpr (HALF)
+        asm volatile(
+            "s_load_dword %0, %4, %6\n\ts_load_dword %1, %4, %7\n\ts_load_dword %2, %5, %6\n\ts_load_dword %3, %5, %7"
+            : "=&s"(kraw[0]), "=&s"(kraw[1]), "=&s"(vraw[0]), "=&s"(vraw[1])
+            : "s"(a.k_scale), "s"(a.v_scale), "s"((unsigned)spid[0] * 4u), "s"((unsigned)spid[1] * 4u));
+      else
       asm volatile(
           "s_load_dword %0, %8, %10\n\ts_load_dword %1, %8, %11\n\ts_load_dword %2, %8, %12\n\ts_load_dword %3, %8, %13\n\t"
           "s_load_dword %4, %9, %10\n\ts_load_dword %5, %9, %11\n\ts_load_dword %6, %9, %12\n\ts_load_dword %7, %9, %13"
-          : "=&s"(kraw[0]), "=&s"(kraw[1]), "=&s"(kraw[2]), "=&s"(kraw[3]), "=&s"(vraw[0]), "=&s"(vraw[1]), "=&s"(vraw[2]), "=&s"(vraw[3])
-          : "s"(a.k_scale), "s"(a.v_scale), "s"((unsigned)spid[0] * 4u), "s"((unsigned)spid[1] * 4u), "s"((unsigned)spid[2] * 4u),
-            "s"((unsigned)spid[3] * 4u));
+          : "=&s"(kraw[0]), "=&s"(kraw[1]), "=&s"(kraw[2 % kPg]), "=&s"(kraw[3 % kPg]), "=&s"(vraw[0]), "=&s"(vraw[1]), "=&s"(vraw[2 % kPg]), "=&s"(vraw[3 % kPg])
+          : "s"(a.k_scale), "s"(a.v_scale), "s"((unsigned)spid[0] * 4u), "s"((unsigned)spid[1] * 4u), "s"((unsigned)spid[2 % kPg] * 4u),
+            "s"((unsigned)spid[3 % kPg] * 4u));
       fetch_spids(i + 2);
     }
   };
@@ -688,10 +714,13 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) { pid_new[j] = __builtin_amdgcn_readfirstlane(pid_new[j]); asm volatile("" : "+s"(pid_new[j])); }   // arrived here, not wherever it is used next
     if constexpr (FP8) {
-      asm volatile("s_waitcnt lgkmcnt(0)"
-                   : "+s"(kraw[0]), "+s"(kraw[1]), "+s"(kraw[2]), "+s"(kraw[3]), "+s"(vraw[0]), "+s"(vraw[1]), "+s"(vraw[2]), "+s"(vraw[3]));
+      if constexpr (HALF)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(kraw[0]), "+s"(kraw[1]), "+s"(vraw[0]), "+s"(vraw[1]));
+      else
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+s"(kraw[0]), "+s"(kraw[1]), "+s"(kraw[2 % kPg]), "+s"(kraw[3 % kPg]), "+s"(vraw[0]), "+s"(vraw[1]), "+s"(vraw[2 % kPg]), "+s"(vraw[3 % kPg]));
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
+      for (int p = 0; p < kPg; ++p) {
         spid[p] = __builtin_amdgcn_readfirstlane(spid[p]);
         asm volatile("" : "+s"(spid[p]));
         ksc_cur[p] = __uint_as_float(kraw[p]) * a.scale_log2;   // the softmax of this block is done with the old ones
@@ -750,8 +779,42 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     }
   };
   if (wave_active) run(std::true_type{}); else run(std::false_type{});
+  if constexpr (HALF) {
+    // The trailing wave of a pair hands over its half of the tile: accumulators, reference and (per-lane) sum.
+    float* mine = merge_s[wave & 3];
+    if (grp == 1 && wave_active) {
+#pragma unroll
+      for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+          *(floatx4*)(mine + ((dt * 4 + i4) * 64 + lane) * 4) = floatx4{acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
+      mine[kDT * 16 * 64 + lane] = m_run;
+      mine[kDT * 16 * 64 + 64 + lane] = l_run;
+    }
+  }
   if (grp == 0) PHASE_END();
   if constexpr (!FP8) DMA_WAIT(0);                   // nothing may still be landing in LDS when the workgroup retires
+  if constexpr (HALF) {
+    __syncthreads();                                   // the trailing waves' results are in LDS
+    if (grp == 1) return;
+    if (wave_active) {
+      const float* theirs = merge_s[wave & 3];
+      const float m2 = theirs[kDT * 16 * 64 + lane], l2 = theirs[kDT * 16 * 64 + 64 + lane];
+      const float m_new = fmaxf(m_run, m2);
+      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+      const float a1 = __builtin_amdgcn_exp2f(m_run - m_safe), a2 = __builtin_amdgcn_exp2f(m2 - m_safe);
+      l_run = l_run * a1 + l2 * a2;
+      m_run = m_new;
+#pragma unroll
+      for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const floatx4 o = *(const floatx4*)(theirs + ((dt * 4 + i4) * 64 + lane) * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[dt][i4 * 4 + e] = acc[dt][i4 * 4 + e] * a1 + o[e] * a2;
+        }
+    }
+  }
 #undef PHASE_END
 #undef BARRIER_RAW
 #undef DMA_WAIT
@@ -778,15 +841,20 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 
 }  // namespace
 
-hipError_t launch_append_mfma(const AppendArgs& a, int head_dim, bool fp8, int grid, hipStream_t s) {
+hipError_t launch_append_mfma(const AppendArgs& a, int head_dim, bool fp8, bool half_tiles, int grid, hipStream_t s) {
+  if (half_tiles && !fp8) return hipErrorInvalidValue;   // (the bf16 tile ring leaves no LDS for the merge buffer)
   if (head_dim == 128 && !fp8) {
-    hipLaunchKernelGGL((append_mfma_kernel<128, false>), dim3(grid), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((append_mfma_kernel<128, false, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 128 && fp8 && !half_tiles) {
+    hipLaunchKernelGGL((append_mfma_kernel<128, true, false>), dim3(grid), dim3(kThreads), 0, s, a);
   } else if (head_dim == 128 && fp8) {
-    hipLaunchKernelGGL((append_mfma_kernel<128, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((append_mfma_kernel<128, true, true>), dim3(grid), dim3(kThreads), 0, s, a);
   } else if (head_dim == 64 && !fp8) {
-    hipLaunchKernelGGL((append_mfma_kernel<64, false>), dim3(grid), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((append_mfma_kernel<64, false, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 64 && fp8 && !half_tiles) {
+    hipLaunchKernelGGL((append_mfma_kernel<64, true, false>), dim3(grid), dim3(kThreads), 0, s, a);
   } else if (head_dim == 64 && fp8) {
-    hipLaunchKernelGGL((append_mfma_kernel<64, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((append_mfma_kernel<64, true, true>), dim3(grid), dim3(kThreads), 0, s, a);
   } else {
     return hipErrorInvalidValue;
   }

@@ -108,7 +108,8 @@ WorkspaceLayout decode_layout(const rollattn_desc& d) {
 WorkspaceLayout append_layout(const rollattn_desc& d, int32_t total_q) {
   WorkspaceLayout w{};
   const int group = d.num_q_heads / d.num_kv_heads;
-  const int tile_tokens = std::max(1, kAppendTileRows / group);
+  // room for the list of half-size tiles too (a call over FP8 pools may choose them)
+  const int tile_tokens = std::max(1, kAppendTileRows / 2 / group);
   w.workers = (int32_t)std::min<int64_t>((int64_t)total_q / tile_tokens + d.batch + 1, INT32_MAX);
   size_t off = 0;
   w.header = off;      off += align256(sizeof(int32_t) * kPlanWords);
@@ -361,7 +362,6 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
   a.q_lens = q_lens; a.q_offsets = q_offsets; a.out = out; a.k_scale = desc->k_scale; a.v_scale = desc->v_scale;
   a.header = (int32_t*)(base + w.header);
   a.tile_rec = (const int32_t*)(base + w.wstart);
-  a.tile_cap = w.workers;
   a.batch = desc->batch; a.hq = desc->num_q_heads; a.hkv = desc->num_kv_heads;
   a.group = desc->num_q_heads / desc->num_kv_heads; a.max_pages = table_stride;
   a.tile_tokens = std::max(1, kAppendTileRows / a.group);
@@ -370,6 +370,9 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
   const bool half_tiles = desc->kv_dtype == ROLLATTN_FP8_E4M3 && desc->q_dtype != ROLLATTN_F32 &&
                           (int64_t)max_q_len * a.group <= kAppendTileRows / 2;
   if (half_tiles) a.tile_tokens = std::max(1, kAppendTileRows / 2 / a.group);
+  // tiles this call can have at most (<= the capacity of the workspace, which is laid out for half tiles)
+  const int32_t tile_cap = (int32_t)std::min<int64_t>((int64_t)total_q / a.tile_tokens + desc->batch + 1, w.workers);
+  a.tile_cap = tile_cap;
   a.total_q = total_q;
   a.scale_log2 = desc->sm_scale * 1.4426950408889634f;
   a.lse = lse;
@@ -385,17 +388,17 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
     if (e != hipSuccess) return fail_hip(e);
     return ROLLATTN_OK;
   }
-  e = launch_plan_append(q_lens, q_offsets, ctx_lens, desc->batch, a.tile_tokens, w.workers, skip_unit_chunks, a.header,
+  e = launch_plan_append(q_lens, q_offsets, ctx_lens, desc->batch, a.tile_tokens, tile_cap, skip_unit_chunks, a.header,
                          (int32_t*)(base + w.wstart), s);
   if (e != hipSuccess) return fail_hip(e);
   {
     ProfileScope prof(s);
     // one workgroup per (tile, KV head); with fewer than 8 heads the kernel deals runs of tiles to the XCDs
     // of a head, which needs up to one run of slack per XCD (see the kernel's index mapping)
-    int64_t grid64 = (int64_t)w.workers * a.hkv;
+    int64_t grid64 = (int64_t)tile_cap * a.hkv;
     if (a.hkv < kXcds && kXcds % a.hkv == 0) {
       const int64_t parts = kXcds / a.hkv;
-      grid64 = kXcds * (((int64_t)w.workers + parts - 1) / parts + kAppendXcdRun);
+      grid64 = kXcds * (((int64_t)tile_cap + parts - 1) / parts + kAppendXcdRun);
     }
     const int grid = (int)std::min<int64_t>(grid64, INT32_MAX);
     e = launch_append_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, half_tiles, grid, s);

@@ -93,6 +93,18 @@ def test_append_half_tiles_over_fp8_pools(name, hq, hkv, d, max_q):
     assert (out.float() - whole.float()).abs().max().item() <= 2e-2
 
 
+def test_append_with_an_understated_max_q_len_is_still_right():
+    # max_q_len = 1 over FP8 pools selects half tiles although the chunks have up to 300 tokens: they are then cut into many
+    # half tiles (causal edges inside them), and the work list has room for them
+    b = W.build(W.Workload("half_many", 6, 32, 2, 128, "bf16", "fp8_e4m3", ("uniform", 0, 700), qlen=("uniform", 1, 300), ctx_is_prefix=True,
+                           seed=W.BASE_SEED + 75), DEV)
+    w = b.workload
+    out = B.attn_append(b.q, b.q_lens, b.q_offsets, b.k_pages, b.v_pages, b.page_table, b.ctx_lens, sm_scale=w.sm_scale,
+                        max_q_len=1, k_scale=b.k_scale, v_scale=b.v_scale)
+    torch.cuda.synchronize()
+    check(out, oracle_append(b), "bf16", "half tiles, many per chunk")
+
+
 @pytest.mark.parametrize("qd,kvd,d", [("f32", "f32", 64), ("bf16", "bf16", 128), ("bf16", "fp8_e4m3", 128)])
 def test_a_context_split_over_two_calls_and_merged(qd, kvd, d):
     # what a second GPU holding the later pages would do: range 1 = the first S_b tokens, range 2 = the rest through a

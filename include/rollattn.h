@@ -127,10 +127,10 @@ int rollattn_static_init(void);
  * chunk and fully to the cached prefix (Section 3.1, the compute-bound prefill phase, on
  * top of the prefix cache of Section 7.1).  ctx_lens INCLUDES the chunk.  q_offsets is the
  * exclusive scan of q_lens ([B+1], device); total_q = q_offsets[B] and max_q_len >=
- * max n_b are host scalars.  max_q_len only picks the tile shape: over FP8 pools, when
- * no chunk has more than 128 / (Hq / Hkv) tokens the call uses half-size tiles that two
- * waves share (same result within rounding, faster); a value that understates the
- * longest chunk costs speed, not correctness.  Requires n_b <= L_b.  With every n_b == 1 the result equals attn_decode.
+ * max n_b are host scalars.  max_q_len only picks the tile shape: when no chunk has
+ * more than 128 / (Hq / Hkv) tokens the call uses half-size tiles that two waves share
+ * (same result within rounding, faster); a value that understates the longest chunk
+ * costs speed, not correctness.  Requires n_b <= L_b.  With every n_b == 1 the result equals attn_decode.
  * total_q == 0 succeeds without a launch. */
 int attn_append(const rollattn_desc *desc, const void *q_chunk, const int32_t *q_lens,
                 const int32_t *q_offsets, int32_t total_q, int32_t max_q_len, const void *k_pages,

@@ -108,7 +108,7 @@ WorkspaceLayout decode_layout(const rollattn_desc& d) {
 WorkspaceLayout append_layout(const rollattn_desc& d, int32_t total_q) {
   WorkspaceLayout w{};
   const int group = d.num_q_heads / d.num_kv_heads;
-  // room for the list of half-size tiles too (a call over FP8 pools may choose them)
+  // room for the list of half-size tiles too (a call whose chunks are all short chooses them)
   const int tile_tokens = std::max(1, kAppendTileRows / 2 / group);
   w.workers = (int32_t)std::min<int64_t>((int64_t)total_q / tile_tokens + d.batch + 1, INT32_MAX);
   size_t off = 0;
@@ -366,9 +366,8 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
   a.group = desc->num_q_heads / desc->num_kv_heads; a.max_pages = table_stride;
   a.tile_tokens = std::max(1, kAppendTileRows / a.group);
   // No chunk longer than half a tile (a few new tokens per trajectory; the members of a group in attn_decode_shared):
-  // half tiles, whose blocks the two waves of a SIMD share (FP8 pools)
-  const bool half_tiles = desc->kv_dtype == ROLLATTN_FP8_E4M3 && desc->q_dtype != ROLLATTN_F32 &&
-                          (int64_t)max_q_len * a.group <= kAppendTileRows / 2;
+  // half tiles, whose blocks the two waves of a SIMD share
+  const bool half_tiles = desc->q_dtype != ROLLATTN_F32 && (int64_t)max_q_len * a.group <= kAppendTileRows / 2;
   if (half_tiles) a.tile_tokens = std::max(1, kAppendTileRows / 2 / a.group);
   // tiles this call can have at most (<= the capacity of the workspace, which is laid out for half tiles)
   const int32_t tile_cap = (int32_t)std::min<int64_t>((int64_t)total_q / a.tile_tokens + desc->batch + 1, w.workers);

@@ -121,9 +121,14 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   __shared__ __attribute__((aligned(1024))) unsigned char k_lds[kRing][kTileBytes];
   __shared__ __attribute__((aligned(1024))) unsigned char v_lds[kRing][kTileBytes];
   // HALF: where the trailing waves leave their result for the leading ones: per wave pair the accumulators
-  // [D / 32][4][64 lanes] as 16-byte quads, then reference and sum
-  constexpr int kMergeFloats = HALF ? (D / 32) * 16 * 64 + 2 * 64 : 1;
-  __shared__ __attribute__((aligned(16))) float merge_s[HALF ? kWaves / 2 : 1][kMergeFloats];
+  // [D / 32][4][64 lanes] as 16-byte quads, and reference and sum.  The accumulators of the four pairs are as large
+  // as four bf16 tiles: over bf16 pools they go into the K ring, which nobody reads or loads into any more by
+  // then (every wave has waited for its last loads, and the last read of a K tile lies before the trailing
+  // waves' last barrier); the two FP8 tiles of the K ring are too small, there the accumulators get LDS of their own.
+  constexpr int kMergeAcc = (D / 32) * 16 * 64;      // floats per wave pair
+  static_assert(!HALF || FP8 || (size_t)kRing * kTileBytes >= (size_t)(kWaves / 2) * kMergeAcc * sizeof(float), "K ring holds the accumulators");
+  __shared__ __attribute__((aligned(16))) float merge_acc_s[HALF && FP8 ? kWaves / 2 : 1][HALF && FP8 ? kMergeAcc : 4];
+  __shared__ float merge_ml_s[HALF ? kWaves / 2 : 1][HALF ? 128 : 1];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -779,17 +784,18 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     }
   };
   if (wave_active) run(std::true_type{}); else run(std::false_type{});
+  float* const mine = !HALF ? nullptr : FP8 ? merge_acc_s[FP8 ? (wave & 3) : 0] : (float*)&k_lds[0][0] + (wave & 3) * kMergeAcc;
+  float* const mine_ml = merge_ml_s[HALF ? (wave & 3) : 0];
   if constexpr (HALF) {
     // The trailing wave of a pair hands over its half of the tile: accumulators, reference and (per-lane) sum.
-    float* mine = merge_s[wave & 3];
     if (grp == 1 && wave_active) {
 #pragma unroll
       for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4)
           *(floatx4*)(mine + ((dt * 4 + i4) * 64 + lane) * 4) = floatx4{acc[dt][i4 * 4], acc[dt][i4 * 4 + 1], acc[dt][i4 * 4 + 2], acc[dt][i4 * 4 + 3]};
-      mine[kDT * 16 * 64 + lane] = m_run;
-      mine[kDT * 16 * 64 + 64 + lane] = l_run;
+      mine_ml[lane] = m_run;
+      mine_ml[64 + lane] = l_run;
     }
   }
   if (grp == 0) PHASE_END();
@@ -798,8 +804,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
     __syncthreads();                                   // the trailing waves' results are in LDS
     if (grp == 1) return;
     if (wave_active) {
-      const float* theirs = merge_s[wave & 3];
-      const float m2 = theirs[kDT * 16 * 64 + lane], l2 = theirs[kDT * 16 * 64 + 64 + lane];
+      const float* theirs = mine;
+      const float m2 = mine_ml[lane], l2 = mine_ml[64 + lane];
       const float m_new = fmaxf(m_run, m2);
       const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
       const float a1 = __builtin_amdgcn_exp2f(m_run - m_safe), a2 = __builtin_amdgcn_exp2f(m2 - m_safe);
@@ -842,15 +848,18 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 }  // namespace
 
 hipError_t launch_append_mfma(const AppendArgs& a, int head_dim, bool fp8, bool half_tiles, int grid, hipStream_t s) {
-  if (half_tiles && !fp8) return hipErrorInvalidValue;   // (the bf16 tile ring leaves no LDS for the merge buffer)
-  if (head_dim == 128 && !fp8) {
+  if (head_dim == 128 && !fp8 && !half_tiles) {
     hipLaunchKernelGGL((append_mfma_kernel<128, false, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 128 && !fp8) {
+    hipLaunchKernelGGL((append_mfma_kernel<128, false, true>), dim3(grid), dim3(kThreads), 0, s, a);
   } else if (head_dim == 128 && fp8 && !half_tiles) {
     hipLaunchKernelGGL((append_mfma_kernel<128, true, false>), dim3(grid), dim3(kThreads), 0, s, a);
   } else if (head_dim == 128 && fp8) {
     hipLaunchKernelGGL((append_mfma_kernel<128, true, true>), dim3(grid), dim3(kThreads), 0, s, a);
-  } else if (head_dim == 64 && !fp8) {
+  } else if (head_dim == 64 && !fp8 && !half_tiles) {
     hipLaunchKernelGGL((append_mfma_kernel<64, false, false>), dim3(grid), dim3(kThreads), 0, s, a);
+  } else if (head_dim == 64 && !fp8) {
+    hipLaunchKernelGGL((append_mfma_kernel<64, false, true>), dim3(grid), dim3(kThreads), 0, s, a);
   } else if (head_dim == 64 && fp8 && !half_tiles) {
     hipLaunchKernelGGL((append_mfma_kernel<64, true, false>), dim3(grid), dim3(kThreads), 0, s, a);
   } else if (head_dim == 64 && fp8) {

@@ -93,7 +93,7 @@ hipError_t launch_plan_append(const int32_t* q_lens, const int32_t* q_offsets, c
 hipError_t launch_decode_f32(const DecodeArgs& a, int head_dim, int grid, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeArgs& a, int head_dim, bool fp8, int grid, hipStream_t s);
 hipError_t launch_combine(const DecodeArgs& a, int head_dim, bool out_bf16, hipStream_t s);
-// half_tiles (FP8 pools only): every tile has at most kAppendTileRows / 2 rows (a.tile_tokens is set accordingly) and the
+// half_tiles: every tile has at most kAppendTileRows / 2 rows (a.tile_tokens is set accordingly) and the
 // two waves of a SIMD split each block of a tile between them instead of owning different rows
 hipError_t launch_append_mfma(const AppendArgs& a, int head_dim, bool fp8, bool half_tiles, int grid, hipStream_t s);
 hipError_t launch_append_f32(const AppendArgs& a, int head_dim, int grid, hipStream_t s);

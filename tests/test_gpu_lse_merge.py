@@ -70,13 +70,14 @@ def test_append_denominators(hq, hkv, d, qd, kvd):
     _check_lse(lse, _oracle_lse(b, b.q_lens_host), qd, "append", tol=LSE_TOL_APPEND_BF16_POOLS if kvd == "bf16" else None)
 
 
+@pytest.mark.parametrize("kvd", ["bf16", "fp8_e4m3"])
 @pytest.mark.parametrize("name,hq,hkv,d,max_q", [("half_g16", 64, 4, 128, 8), ("half_g1", 8, 8, 128, 128), ("half_d64_g8", 16, 2, 64, 16),
                                                  ("half_g40", 40, 1, 64, 3)])
-def test_append_half_tiles_over_fp8_pools(name, hq, hkv, d, max_q):
-    # No chunk fills more than half a query tile, FP8 pools: the kernel then lets the two waves of a SIMD split every KV block
+def test_append_half_tiles(name, hq, hkv, d, max_q, kvd):
+    # No chunk fills more than half a query tile: the kernel then lets the two waves of a SIMD split every KV block
     # (32 tokens each) and merges their two running states when the tile ends.  Prefixes from 0 on: in contexts of up to 32
     # tokens the second wave of a pair sees nothing at all, in ragged last blocks only part of its share.
-    b = W.build(W.Workload(name, 40, hq, hkv, d, "bf16", "fp8_e4m3", ("uniform", 0, 300), qlen=("uniform", 1, max_q), ctx_is_prefix=True,
+    b = W.build(W.Workload(name, 40, hq, hkv, d, "bf16", kvd, ("uniform", 0, 300), qlen=("uniform", 1, max_q), ctx_is_prefix=True,
                            seed=W.BASE_SEED + 74), DEV)
     assert int(b.q_lens_host.max()) * (hq // hkv) <= 128 and b.ctx_lens_host.min() <= 64 and b.ctx_lens_host.max() > 256
     w = b.workload
@@ -84,7 +85,7 @@ def test_append_half_tiles_over_fp8_pools(name, hq, hkv, d, max_q):
                                  max_q_len=int(b.q_lens_host.max()), k_scale=b.k_scale, v_scale=b.v_scale)
     torch.cuda.synchronize()
     check(out, oracle_append(b), "bf16", name)
-    _check_lse(lse, _oracle_lse(b, b.q_lens_host), "bf16", name)
+    _check_lse(lse, _oracle_lse(b, b.q_lens_host), "bf16", name, tol=LSE_TOL_APPEND_BF16_POOLS if kvd == "bf16" else None)
     # a max_q_len above half a tile selects whole tiles: same rows, the other kernel variant, the same result within rounding
     whole = B.attn_append(b.q, b.q_lens, b.q_offsets, b.k_pages, b.v_pages, b.page_table, b.ctx_lens, sm_scale=w.sm_scale,
                           max_q_len=256, k_scale=b.k_scale, v_scale=b.v_scale)
@@ -94,7 +95,7 @@ def test_append_half_tiles_over_fp8_pools(name, hq, hkv, d, max_q):
 
 
 def test_append_with_an_understated_max_q_len_is_still_right():
-    # max_q_len = 1 over FP8 pools selects half tiles although the chunks have up to 300 tokens: they are then cut into many
+    # max_q_len = 1 selects half tiles although the chunks have up to 300 tokens: they are then cut into many
     # half tiles (causal edges inside them), and the work list has room for them
     b = W.build(W.Workload("half_many", 6, 32, 2, 128, "bf16", "fp8_e4m3", ("uniform", 0, 700), qlen=("uniform", 1, 300), ctx_is_prefix=True,
                            seed=W.BASE_SEED + 75), DEV)

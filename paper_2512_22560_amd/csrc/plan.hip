@@ -127,26 +127,45 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
     }
     __syncthreads();
   }
+  __shared__ int first_s[kPlanThreads], count_s[kPlanThreads], b_s[kPlanThreads], qlen_s[kPlanThreads], ctx_s[kPlanThreads],
+      qoff_s[kPlanThreads];
   int running = 0;
   for (int p0 = 0; p0 < batch; p0 += kPlanThreads) {
     const int p = p0 + tid;
-    int b = 0, count = 0;
+    int b = 0, count = 0, q_len = 0;
     if (p < batch) {
       b = ranked ? order_s[p] : p;
-      count = (q_lens[b] + tile_tokens - 1) / tile_tokens;
-      if (skip_unit_chunks && q_lens[b] == 1) count = 0;   // mixed step: the decode kernel takes these
+      q_len = q_lens[b];
+      count = (q_len + tile_tokens - 1) / tile_tokens;
+      if (skip_unit_chunks && q_len == 1) count = 0;   // mixed step: the decode kernel takes these
     }
     int tile_total;
     const int first = running + block_exclusive_scan(count, wave_tot, &tile_total);
+    first_s[tid] = first;
+    count_s[tid] = count;
+    b_s[tid] = b;
+    qlen_s[tid] = q_len;
+    ctx_s[tid] = p < batch ? ctx_lens[b] : 0;
+    qoff_s[tid] = p < batch ? q_offsets[b] : 0;
+    __syncthreads();
     // One 32-byte record per tile with everything the tile's workgroup needs to start, so that it gets there with
-    // one dependent load instead of a chain of them: (b, first row, n_b, L_b, q_offsets[b]).
-    for (int s = 0; s < count; ++s) {
-      if (first + s < cap) {
-        int4* rec = (int4*)(tile_rec + (size_t)(first + s) * kTileRecWords);
-        rec[0] = make_int4(b, (count - 1 - s) * tile_tokens, q_lens[b], ctx_lens[b]);   // a chunk's last tile sees the most context
-        rec[1] = make_int4(q_offsets[b], 0, 0, 0);
+    // one dependent load instead of a chain of them: (b, first row, n_b, L_b, q_offsets[b]).  The tiles of these
+    // trajectories are dealt to the threads one by one (a trajectory may have hundreds): a tile finds its
+    // trajectory as the last one of the group that starts at or before it (those without tiles start where the
+    // next one starts, and are never the last such).
+    const int end = min(running + tile_total, cap);
+    for (int t = running + tid; t < end; t += kPlanThreads) {
+      int lo = 0, hi = kPlanThreads;
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (first_s[mid] <= t) lo = mid; else hi = mid;
       }
+      const int s = t - first_s[lo];
+      int4* rec = (int4*)(tile_rec + (size_t)t * kTileRecWords);
+      rec[0] = make_int4(b_s[lo], (count_s[lo] - 1 - s) * tile_tokens, qlen_s[lo], ctx_s[lo]);   // a chunk's last tile sees the most context
+      rec[1] = make_int4(qoff_s[lo], 0, 0, 0);
     }
+    __syncthreads();
     running += tile_total;
   }
   if (tid == 0) header[kPlanTiles] = running < cap ? running : cap;

@@ -37,6 +37,10 @@
 //     whose addend carries minus the reference), and the V scale of the page is folded into that
 //     addend as log2(vs), so P comes out of the exponential already weighted for the second
 //     product; the row sum divides each page's share by vs again (four multiplies per block).
+//
+// Half tiles.  A call whose chunks all fit into 128 rows gets tiles of 128 rows: waves w and w + 4 then own the
+// same 32 rows and split every block, 32 tokens each, and their two running states are merged when the
+// tile ends (see the template parameter HALF below).
 #include <type_traits>
 #include <utility>
 

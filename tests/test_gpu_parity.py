@@ -189,11 +189,13 @@ def test_device_plan_equals_host_twin_and_oracle_rule(seed, batch, hi, group):
     assert np.array_equal(h_segs, o_segs)
 
 
-@pytest.mark.parametrize("seed,batch,group,max_q,step", [(1, 64, 4, 1024, False), (2, 7, 1, 5, False), (3, 500, 16, 300, True),
-                                                        (4, 4096, 8, 40, False), (5, 4097, 8, 40, True), (6, 33, 256, 9, False),
-                                                        (7, 40, 3, 200, True)])
-def test_device_append_tile_list_equals_the_oracle_rule(seed, batch, group, max_q, step):
+@pytest.mark.parametrize("seed,batch,group,max_q,step,half", [
+    (1, 64, 4, 1024, False, False), (2, 7, 1, 5, False, False), (3, 500, 16, 300, True, False), (4, 4096, 8, 40, False, False),
+    (5, 4097, 8, 40, True, False), (6, 33, 256, 9, False, False), (7, 40, 3, 200, True, False),
+    (8, 64, 4, 300, False, True), (9, 1500, 16, 40, True, True)])
+def test_device_append_tile_list_equals_the_oracle_rule(seed, batch, group, max_q, step, half):
     # the list the append kernel's workgroups take in order: which (trajectory, first row) tiles, and in which order
+    # (half: the call is told max_q_len = 1 and so cuts the chunks into tiles of half the rows)
     rng = np.random.default_rng(seed)
     q_lens = rng.integers(0, max_q + 1, batch).astype(np.int32)
     if step:
@@ -210,7 +212,9 @@ def test_device_append_tile_list_equals_the_oracle_rule(seed, batch, group, max_
     pt = torch.zeros((batch, max_pages), dtype=torch.int32, device=DEV)
     args = (torch.from_numpy(q_lens).to(DEV), torch.from_numpy(offs).to(DEV), kp, kp, pt, torch.from_numpy(ctx).to(DEV))
     desc = B.make_desc(q, kp, pt, sm_scale=1.0)
-    tile_tokens = max(1, 256 // group)
+    tile_tokens = max(1, (128 if half else 256) // group)
+    if half:
+        max_q = 1
     if step:
         n = int(B.lib().rollattn_step_workspace_bytes(ctypes.byref(desc), total_q))
         ws = torch.empty(n, dtype=torch.uint8, device=DEV)

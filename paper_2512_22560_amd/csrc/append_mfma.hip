@@ -829,22 +829,31 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #undef BARRIER_RAW
 #undef DMA_WAIT
 
-  // ---- normalise and store: lane (row n32, half h2) owns dims dt*32 + (i/4)*8 + h2*4 + i%4
+  // ---- normalise and store: lane (row n32, half h2) owns dims dt*32 + (i/4)*8 + h2*4 + i%4, four dims at a
+  // time.  The two lanes of a row first trade every other group of four, so that each holds runs of eight dims
+  // and stores 16 bytes at a time: half as many store instructions, each of which touches 32 rows.
   l_run = xor32_add(l_run);
-  if (row_ok) {
-    // log2 of the row's softmax denominator, for callers that merge this result with another range's
-    if (a.lse && h2 == 0) a.lse[(size_t)(q_off + q0 + tok_in_tile) * a.hq + head] = m_run + __builtin_amdgcn_logf(l_run);
-    const float inv = 1.f / l_run;
-    __bf16* orow = (__bf16*)a.out + ((size_t)(q_off + q0 + tok_in_tile) * a.hq + head) * D;
+  const float inv = 1.f / l_run;
+  // log2 of the row's softmax denominator, for callers that merge this result with another range's
+  if (row_ok && a.lse && h2 == 0) a.lse[(size_t)(q_off + q0 + tok_in_tile) * a.hq + head] = m_run + __builtin_amdgcn_logf(l_run);
+  __bf16* orow = (__bf16*)a.out + ((size_t)(q_off + q0 + tok_in_tile) * a.hq + head) * D;
 #pragma unroll
-    for (int dt = 0; dt < kDT; ++dt) {
+  for (int dt = 0; dt < kDT; ++dt) {
+    uintx2 g[4];
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        bf16x4 pk;
+    for (int i4 = 0; i4 < 4; ++i4) {
+      bf16x4 pk;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(acc[dt][i4 * 4 + e] * inv);
-        *(bf16x4*)(orow + dt * 32 + i4 * 8 + h2 * 4) = pk;
-      }
+      for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(acc[dt][i4 * 4 + e] * inv);
+      g[i4] = __builtin_bit_cast(uintx2, pk);
+    }
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      // h2 = 0 keeps its group 2 pr (dims 8 pr .. + 3 of the 16) and gets the other lane's; h2 = 1 gets this lane's group
+      // 2 pr + 1 and keeps its own: lower lane dims 16 pr + 0 .. 7, upper lane dims 16 pr + 8 .. 15
+      const uintx2 w0 = __builtin_amdgcn_permlane32_swap(g[2 * pr][0], g[2 * pr + 1][0], false, false);
+      const uintx2 w1 = __builtin_amdgcn_permlane32_swap(g[2 * pr][1], g[2 * pr + 1][1], false, false);
+      if (row_ok) *(uintx4*)(orow + dt * 32 + pr * 16 + h2 * 8) = uintx4{w0[0], w1[0], w0[1], w1[1]};
     }
   }
 }

@@ -102,6 +102,32 @@ def test_fp8_pools_codes_and_scales_over_three_turns(hkv, d):
     assert np.isfinite(W.raw_numpy(state[2])[np.unique(W.raw_numpy(b1.page_table)[W.raw_numpy(b1.page_table) >= 0])]).all()
 
 
+def test_fp8_codes_for_bf16_values_of_every_magnitude():
+    # The kernel divides every new element by its page's scale; for scales of moderate magnitude it does so with a reciprocal
+    # shared by the page and the correction steps of an IEEE division.  Pages whose values sit anywhere between the smallest
+    # and the largest bf16 exponents (scales from 2^-135 to 2^118: both sides of the range where the shortcut applies), with
+    # arbitrary mantissas, signs, zeros and subnormals below the page's maximum: codes and scales bit for bit.
+    rng = np.random.default_rng(77)
+    batch, hkv, d = 384, 2, 64
+    w0 = _wl("kvw_mag", batch, hkv, d, "bf16", "fp8_e4m3", ("const", 0), ("uniform", 1, 48), 305)
+    b = W.build(w0, DEV)
+    kp = torch.full_like(b.k_pages, 0x7F); vp = torch.full_like(b.v_pages, 0x7F)
+    ks = torch.full_like(b.k_scale, float("nan")); vs = torch.full_like(b.v_scale, float("nan"))
+    def rows():
+        top = rng.integers(1, 255, size=(b.total_q, 1, 1))                  # biased exponent the token's values reach at most
+        exp = np.maximum(top - rng.integers(0, 40, size=(b.total_q, hkv, d)), 0)
+        bits = (rng.integers(0, 2, size=exp.shape) << 15) | (exp << 7) | rng.integers(0, 128, size=exp.shape)
+        bits[rng.random(exp.shape) < 0.02] = 0
+        return torch.from_numpy(bits.astype(np.uint16).view(np.int16)).view(torch.bfloat16).to(DEV)
+    k_new, v_new = rows(), rows()
+    gpu, ref = _run_both(b, k_new, v_new, kp, vp, ks, vs)
+    _assert_same(gpu, ref, "fp8 codes, every magnitude")
+    used = np.unique(W.raw_numpy(b.page_table)[W.raw_numpy(b.page_table) >= 0])
+    sc = W.raw_numpy(gpu[2])[used]
+    sc = sc[np.isfinite(sc)]
+    assert (sc < 2.0 ** -100).any() and (sc > 2.0 ** 100).any() and ((sc > 2.0 ** -20) & (sc < 2.0 ** 20)).any()
+
+
 def test_fp8_decode_step_writes_one_token_per_trajectory():
     b = W.build(W.Workload("kvw1", 300, 8, 4, 128, "bf16", "fp8_e4m3", ("uniform", 1, 200), seed=303), DEV)
     k_new, v_new = _new_rows(b, 5, (0.1, 1.0, 20.0))

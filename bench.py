@@ -21,7 +21,10 @@ the call's stream and lets the library bracket its main kernel: the per-leg kern
 whole-call figures (mean, median, minimum) all come from that one pass.  Fractions are given
 against the nominal peaks (HBM 8 TB/s, dense bf16 MFMA 2.5 PFLOP/s) and against what two
 microbenchmarks of libbench_peaks.so reach on this GPU in this run (a streaming read of 4 GiB
-and a register-resident MFMA loop).
+and a register-resident MFMA loop).  Legs that run the MFMA append kernel also report the shader clock that kernel
+got ("append_kernel_clock_mhz": cycles over ticks of the constant 100 MHz counter, summed inside its tiles by the
+library while profiling is on) and their fraction of the peak at that clock: the part runs these kernels at its
+power limit, well below the 2.4 GHz that the nominal peak assumes.
 
 The "roofline" object is for the main kernel of the headline workload.  "cpu_baseline" is the
 float64 oracle, untuned, on the host cores of the same box, on the same bytes;
@@ -45,6 +48,7 @@ sys.path.insert(0, ROOT)
 METRIC = "decode-attn achieved HBM GB/s (% of peak) + append TFLOP/s, ragged paged KV"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+NOMINAL_CLOCK_MHZ = 2400.0      # the clock that peak is quoted at
 HEADLINE = 2
 # HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, each scaled by its
 # reading on a copy of known size).  They cannot be taken inside this program; profiles/hbm_traffic.json keeps
@@ -229,6 +233,7 @@ def time_legs(legs, steps, warmup, B):
             marks[li].append((a, b))
     torch.cuda.synchronize()
     kernel_all = B.profile_read()
+    append_clock = B.profile_append_clock()     # MHz over this pass's MFMA append launches, 0.0 without any
     B.profile_enable(False)
     per_step = sum(2 if leg.kind in ("decode_shared", "step") else 1 for leg in legs)   # main kernels per step, in launch order
     kernel_all = np.asarray(kernel_all[: len(kernel_all) // per_step * per_step]).reshape(-1, per_step)
@@ -239,7 +244,7 @@ def time_legs(legs, steps, warmup, B):
         col += n
         call = np.asarray([a.elapsed_time(b) for a, b in marks[li]])
         out.append((kms, call))
-    return ms_per_step, out, graph_ms
+    return ms_per_step, out, graph_ms, append_clock
 
 
 def _stats(x):
@@ -438,11 +443,17 @@ def main():
         batch = W.build(w, dev)
         small = W.algorithmic_work(w, batch.ctx_lens_host, batch.q_lens_host)["kv_bytes"] < 2e9
         legs = [Leg(kind, bb, B, W, n_pools=3 if small else 1) for kind, bb in _parts(batch, c, W)]
-        ms, timed, gms = time_legs(legs, a.steps, a.warmup, B)
+        ms, timed, gms, append_clock = time_legs(legs, a.steps, a.warmup, B)
         leg_reps = [leg_report(l, k, call, peaks, ms if len(legs) == 1 else None) for l, (k, call) in zip(legs, timed)]
         for l, r in zip(legs, leg_reps):
             if r["kind"] in MAIN_KERNEL_SOURCES:
                 r["hbm_traffic_bytes"] = counter_traffic(w.name, r["kind"])
+            if append_clock and r["kind"] in ("append", "step", "decode_shared"):
+                # the clock the MFMA append kernel got in the profiled pass (counted inside its tiles); at a lower
+                # clock than the nominal one the nominal peak is out of reach by that factor
+                r["append_kernel_clock_mhz"] = append_clock
+                if r["bound"] == "mfma":
+                    r["frac_of_peak_at_that_clock"] = r["frac"] * NOMINAL_CLOCK_MHZ / append_clock
         rep = {"ms_per_step": ms, "graph_ms_per_step": gms, "steps": a.steps, "legs": leg_reps,
                "batch": w.batch, "heads": [w.num_q_heads, w.num_kv_heads, w.head_dim], "kv_dtype": w.kv_dtype,
                "tokens": int(batch.ctx_lens_host.sum()), "query_rows": int(batch.q_lens_host.sum())}

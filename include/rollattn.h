@@ -291,6 +291,11 @@ size_t rollattn_step_append_offset(const rollattn_desc *desc);
  * returns up to `cap` durations in milliseconds, oldest first, and makes the pairs available again. */
 int rollattn_profile_enable(int on);
 int rollattn_profile_read(float *ms_out, int cap);
+/* While profiling is on, the MFMA append kernel also counts, per tile, shader-clock cycles and ticks of the GPU's
+ * constant 100 MHz counter (two 8-byte sums in a device variable of the library, on the device that was current
+ * when profiling was switched on).  This call synchronises the device, sets *mhz_out (host) to the clock those
+ * sums give for all append launches since the last call, 0 if there were none, and clears the sums. */
+int rollattn_profile_append_clock(double *mhz_out);
 
 const char *rollattn_status_string(int status);
 const char *rollattn_last_hip_error(void);

@@ -24,7 +24,7 @@ EXPORTS = (
     "rollattn_step_workspace_bytes", "rollattn_shared_workspace_bytes", "rollattn_debug_gather",
     "rollattn_debug_check_inputs",
     "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan", "rollattn_debug_read_append_plan", "rollattn_append_plan_capacity", "rollattn_step_append_offset",
-    "rollattn_profile_enable", "rollattn_profile_read", "rollattn_status_string",
+    "rollattn_profile_enable", "rollattn_profile_read", "rollattn_profile_append_clock", "rollattn_status_string",
     "rollattn_last_hip_error", "rollattn_version",
 )
 
@@ -111,6 +111,8 @@ def lib() -> ctypes.CDLL:
         l.rollattn_profile_enable.restype = ctypes.c_int
         l.rollattn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int]
         l.rollattn_profile_read.restype = ctypes.c_int
+        l.rollattn_profile_append_clock.argtypes = [ctypes.POINTER(ctypes.c_double)]
+        l.rollattn_profile_append_clock.restype = ctypes.c_int
         l.rollattn_status_string.argtypes = [ctypes.c_int]
         l.rollattn_status_string.restype = ctypes.c_char_p
         l.rollattn_last_hip_error.argtypes = []
@@ -407,3 +409,12 @@ def profile_read(cap: int = 1024) -> np.ndarray:
     buf = (ctypes.c_float * cap)()
     n = lib().rollattn_profile_read(buf, cap)
     return np.frombuffer(buf, dtype=np.float32, count=n).copy()
+
+
+def profile_append_clock() -> float:
+    """Shader clock (MHz) the MFMA append kernel ran at over the profiled launches since the last call; 0.0 if none."""
+    mhz = ctypes.c_double(0.0)
+    rc = lib().rollattn_profile_append_clock(ctypes.byref(mhz))
+    if rc != 0:
+        raise RollattnError(rc, "rollattn_profile_append_clock")
+    return float(mhz.value)

@@ -16,6 +16,8 @@
 // hipGetSymbolAddress; the device address it stands for is looked up once per device (static_scratch_ptr).
 constexpr size_t kStaticScratchBytes = (size_t)36 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+// Profiling only: what the append kernel adds up while profiling is on (shader-clock cycles, constant-rate ticks).
+static __device__ unsigned long long clock_sums[2];
 
 namespace rollattn {
 
@@ -65,6 +67,7 @@ int check_desc(const rollattn_desc* d, bool need_scales = true) {
 // (events recorded during capture cannot be read back).
 std::vector<EventPair> g_pool;
 size_t g_used = 0;
+unsigned long long* g_clock_sums = nullptr;   // device address of clock_sums on the device profiling was switched on for
 
 struct ProfileScope {
   hipStream_t s;
@@ -376,6 +379,7 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
   a.scale_log2 = desc->sm_scale * 1.4426950408889634f;
   a.lse = lse;
   a.noncausal = noncausal ? 1 : 0;
+  a.clock_sums = nullptr;
 
   hipError_t e;
   if (desc->q_dtype == ROLLATTN_F32) {
@@ -400,6 +404,7 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
       grid64 = kXcds * (((int64_t)tile_cap + parts - 1) / parts + kAppendXcdRun);
     }
     const int grid = (int)std::min<int64_t>(grid64, INT32_MAX);
+    if (prof.on) a.clock_sums = g_clock_sums;
     e = launch_append_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, half_tiles, grid, s);
     prof.stop();
   }
@@ -658,7 +663,35 @@ int rollattn_profile_enable(int on) {
       g_pool.push_back(ev);
     }
   }
+  if (on && !g_clock_sums) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(clock_sums));
+    if (e == hipSuccess) e = hipMemset(p, 0, 2 * sizeof(unsigned long long));
+    if (e != hipSuccess) {
+      g_hip_error = hipGetErrorString(e);
+      return ROLLATTN_EHIP;
+    }
+    g_clock_sums = (unsigned long long*)p;
+  }
   g_profile = on != 0;
+  return ROLLATTN_OK;
+}
+
+int rollattn_profile_append_clock(double* mhz_out) {
+  if (!mhz_out) return ROLLATTN_EINVAL;
+  *mhz_out = 0.0;
+  unsigned long long* p;
+  {
+    std::lock_guard<std::mutex> lk(g_mu);
+    p = g_clock_sums;
+  }
+  if (!p) return ROLLATTN_OK;
+  unsigned long long sums[2] = {0, 0};
+  hipError_t e = hipDeviceSynchronize();
+  if (e == hipSuccess) e = hipMemcpy(sums, p, sizeof(sums), hipMemcpyDeviceToHost);
+  if (e == hipSuccess) e = hipMemset(p, 0, sizeof(sums));
+  if (e != hipSuccess) return fail_hip(e);
+  if (sums[1]) *mhz_out = 100.0 * (double)sums[0] / (double)sums[1];
   return ROLLATTN_OK;
 }
 

@@ -166,6 +166,11 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
   const const_rec_p rec = (const_rec_p)(a.tile_rec + (size_t)min(tile, a.tile_cap - 1) * kTileRecWords);
   const int b = rec[0], q0 = rec[1], n_b = rec[2], ctx = rec[3], q_off = rec[4];
   if (tile >= n_tiles) return;
+  __shared__ long clock_s[2];
+  if (a.clock_sums && threadIdx.x == 0) {
+    clock_s[0] = __builtin_amdgcn_s_memtime();
+    clock_s[1] = __builtin_amdgcn_s_memrealtime();
+  }
   const int tokens_here = min(tile_tokens, n_b - q0);
   const int rows_here = tokens_here * group;
   // Causal mode: row i of the chunk sits at position L_b - n_b + i and sees tokens up to itself.
@@ -855,6 +860,10 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
       const uintx2 w1 = __builtin_amdgcn_permlane32_swap(g[2 * pr][1], g[2 * pr + 1][1], false, false);
       if (row_ok) *(uintx4*)(orow + dt * 32 + pr * 16 + h2 * 8) = uintx4{w0[0], w1[0], w0[1], w1[1]};
     }
+  }
+  if (a.clock_sums && threadIdx.x == 0) {
+    atomicAdd(a.clock_sums, (unsigned long long)(__builtin_amdgcn_s_memtime() - clock_s[0]));
+    atomicAdd(a.clock_sums + 1, (unsigned long long)(__builtin_amdgcn_s_memrealtime() - clock_s[1]));
   }
 }
 

@@ -82,6 +82,9 @@ struct AppendArgs {
   float scale_log2;
   float* lse;           // optional [total_q][Hq], as in DecodeArgs
   int32_t noncausal;    // every row sees all of [0, L_b); the rows' own tokens are not in that range
+  // Optional (profiling): two sums over the launch's tiles as wave 0 sees them, shader-clock cycles and ticks of the
+  // constant-rate counter; their ratio is the clock the kernel ran at.
+  unsigned long long* clock_sums;
 };
 
 // Launchers (defined in the .hip files).  Each returns the hipError_t of its launch.

@@ -116,6 +116,9 @@ def test_descriptor_errors_are_reported_before_any_launch():
     assert lib.rollattn_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 4) == 0
     assert lib.rollattn_workspace_bytes(ctypes.byref(_desc()), 4) > 0
     assert lib.rollattn_profile_read(None, 0) == 0
+    assert lib.rollattn_profile_append_clock(None) == -1
+    mhz = ctypes.c_double(-1.0)
+    assert lib.rollattn_profile_append_clock(ctypes.byref(mhz)) == 0 and mhz.value == 0.0     # profiling never switched on
 
 
 @pytest.mark.parametrize("seed", range(8))

@@ -156,3 +156,23 @@ def test_merge_edges():
     B.attn_merge(o1, l1, o2, l2, out=o1, lse_out=l1)
     torch.cuda.synchronize()
     assert torch.equal(o1, keep) and torch.equal(l1, lse)
+
+
+def test_profiling_reports_the_append_kernels_clock():
+    # while profiling is on the MFMA append kernel counts cycles and constant-rate ticks inside its tiles
+    b = W.build(W.Workload("clk", 8, 32, 8, 128, "bf16", "bf16", ("uniform", 200, 900), qlen=("uniform", 64, 300), ctx_is_prefix=True,
+                           seed=W.BASE_SEED + 76), DEV)
+    plain = gpu_append(b)
+    B.profile_enable(True)
+    try:
+        B.profile_read()
+        B.profile_append_clock()
+        timed = gpu_append(b)
+        torch.cuda.synchronize()
+        assert len(B.profile_read()) == 1
+        mhz = B.profile_append_clock()
+        assert 300.0 < mhz < 2600.0, mhz
+        assert B.profile_append_clock() == 0.0          # read and cleared
+    finally:
+        B.profile_enable(False)
+    assert torch.equal(plain, timed)

@@ -68,6 +68,7 @@ int check_desc(const rollattn_desc* d, bool need_scales = true) {
 std::vector<EventPair> g_pool;
 size_t g_used = 0;
 unsigned long long* g_clock_sums = nullptr;   // device address of clock_sums on the device profiling was switched on for
+int g_clock_dev = -1;                         // ... and that device: launches on other devices do not count
 
 struct ProfileScope {
   hipStream_t s;
@@ -404,7 +405,8 @@ static int append_impl(const rollattn_desc* desc, const void* q_chunk, const int
       grid64 = kXcds * (((int64_t)tile_cap + parts - 1) / parts + kAppendXcdRun);
     }
     const int grid = (int)std::min<int64_t>(grid64, INT32_MAX);
-    if (prof.on) a.clock_sums = g_clock_sums;
+    int dev = -1;
+    if (prof.on && hipGetDevice(&dev) == hipSuccess && dev == g_clock_dev) a.clock_sums = g_clock_sums;
     e = launch_append_mfma(a, desc->head_dim, desc->kv_dtype == ROLLATTN_FP8_E4M3, half_tiles, grid, s);
     prof.stop();
   }
@@ -665,13 +667,16 @@ int rollattn_profile_enable(int on) {
   }
   if (on && !g_clock_sums) {
     void* p = nullptr;
-    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(clock_sums));
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetSymbolAddress(&p, HIP_SYMBOL(clock_sums));
     if (e == hipSuccess) e = hipMemset(p, 0, 2 * sizeof(unsigned long long));
     if (e != hipSuccess) {
       g_hip_error = hipGetErrorString(e);
       return ROLLATTN_EHIP;
     }
     g_clock_sums = (unsigned long long*)p;
+    g_clock_dev = dev;
   }
   g_profile = on != 0;
   return ROLLATTN_OK;

@@ -594,8 +594,8 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
 #define PHASE_END() do { __builtin_amdgcn_sched_barrier(0); BARRIER_RAW(); __builtin_amdgcn_sched_barrier(0); } while (0)
   constexpr std::integral_constant<int, 0> even{};
   constexpr std::integral_constant<int, 1> odd{};
-  constexpr std::integral_constant<int, kPvSteps> c16{};   // first step of the first product
-  constexpr std::integral_constant<int, kSteps> c32{};     // end of the phase
+  constexpr std::integral_constant<int, kPvSteps> c_pv{};   // first step of the first product
+  constexpr std::integral_constant<int, kSteps> c_end{};     // end of the phase
   // Page ids run ahead of the tile loads, so that no load ever waits for an address: U = i + kLead being
   // the unit whose loads a wave starts in its vector phase of block i, toff holds (on entry to that
   // phase) the tile offsets of block U and pid_new the page ids of block U + 1.
@@ -776,19 +776,19 @@ __global__ __launch_bounds__(kThreads) void append_mfma_kernel(const AppendArgs 
       PHASE_END();
       next_block();
     };
-    matrix(c16, c32, even);                          // block 0 has no predecessor: scores only
+    matrix(c_pv, c_end, even);                          // block 0 has no predecessor: scores only
     vector(0, even);
     for (int i = 1; i < n_blocks; i += 2) {
-      matrix(c0, c32, odd);
+      matrix(c0, c_end, odd);
       vector(i, odd);
       if (i + 1 < n_blocks) {
-        matrix(c0, c32, even);
+        matrix(c0, c_end, even);
         vector(i + 1, even);
       }
     }
     if constexpr (kActive) {
       __builtin_amdgcn_s_setprio(1);
-      matrix_phase(c0, c16, 0, ko[kRing - 1], [](auto) {});
+      matrix_phase(c0, c_pv, 0, ko[kRing - 1], [](auto) {});
       __builtin_amdgcn_s_setprio(0);
     }
   };

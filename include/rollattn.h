@@ -260,6 +260,13 @@ int rollattn_debug_plan(const rollattn_desc *desc, const int32_t *ctx_lens_host,
                         int32_t *total_out, int32_t *segments_out, int32_t *n_segments);
 int32_t rollattn_plan_capacity(const rollattn_desc *desc);
 int32_t rollattn_plan_workers(const rollattn_desc *desc);
+/* Testing aid: from now on every decode partition of this process (attn_decode and its variants, the decode rows
+ * of attn_step, the private half of attn_decode_shared, rollattn_debug_plan) is cut for min(workers, all) workers
+ * instead of all of them; the rest of the launch finds no blocks.  One worker walks every row in turn, a few
+ * cut rows at odd places, all of them cut short rows many times: the results must agree whatever the number
+ * (Section 3.1's decoding step does not depend on how the context is split).  0 restores the default.  Returns
+ * the previous setting.  rollattn_plan_workers() reports the number in force. */
+int32_t rollattn_debug_set_decode_workers(int32_t workers);
 
 /* Copies the plan the last attn_decode call left in `workspace` back to the host
  * (synchronises the stream): per, T, and 4 int32 per worker, (b, r << 20 | block, L_b, blocks

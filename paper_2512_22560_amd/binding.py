@@ -23,7 +23,7 @@ EXPORTS = (
     "kv_write", "rollattn_workspace_bytes",
     "rollattn_step_workspace_bytes", "rollattn_shared_workspace_bytes", "rollattn_debug_gather",
     "rollattn_debug_check_inputs",
-    "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan", "rollattn_debug_read_append_plan", "rollattn_append_plan_capacity", "rollattn_step_append_offset",
+    "rollattn_debug_plan", "rollattn_plan_capacity", "rollattn_plan_workers", "rollattn_debug_read_plan", "rollattn_debug_set_decode_workers", "rollattn_debug_read_append_plan", "rollattn_append_plan_capacity", "rollattn_step_append_offset",
     "rollattn_profile_enable", "rollattn_profile_read", "rollattn_profile_append_clock", "rollattn_status_string",
     "rollattn_last_hip_error", "rollattn_version",
 )
@@ -107,6 +107,8 @@ def lib() -> ctypes.CDLL:
         l.rollattn_append_plan_capacity.restype = ctypes.c_int32
         l.rollattn_step_append_offset.argtypes = [dp]
         l.rollattn_step_append_offset.restype = ctypes.c_size_t
+        l.rollattn_debug_set_decode_workers.argtypes = [ctypes.c_int32]
+        l.rollattn_debug_set_decode_workers.restype = ctypes.c_int32
         l.rollattn_profile_enable.argtypes = [ctypes.c_int]
         l.rollattn_profile_enable.restype = ctypes.c_int
         l.rollattn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int]
@@ -418,3 +420,8 @@ def profile_append_clock() -> float:
     if rc != 0:
         raise RollattnError(rc, "rollattn_profile_append_clock")
     return float(mhz.value)
+
+
+def set_decode_workers(workers: int) -> int:
+    """Testing aid: cut every decode partition for this many workers (0: the default, all of them); returns the previous setting."""
+    return int(lib().rollattn_debug_set_decode_workers(int(workers)))

@@ -67,6 +67,7 @@ int check_desc(const rollattn_desc* d, bool need_scales = true) {
 // (events recorded during capture cannot be read back).
 std::vector<EventPair> g_pool;
 size_t g_used = 0;
+int32_t g_debug_workers = 0;                  // testing: decode plans are cut for this many workers (0: all of them)
 unsigned long long* g_clock_sums = nullptr;   // device address of clock_sums on the device profiling was switched on for
 int g_clock_dev = -1;                         // ... and that device: launches on other devices do not count
 
@@ -107,6 +108,12 @@ WorkspaceLayout decode_layout(const rollattn_desc& d) {
   w.partial_o = off;   off += align256(sizeof(float) * 2 * (size_t)w.workers * w.head_tile * d.head_dim);
   w.total = off;
   return w;
+}
+
+// Workers the decode partition is cut for: all of them, unless rollattn_debug_set_decode_workers says fewer.
+static int32_t plan_workers(const WorkspaceLayout& w) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  return (g_debug_workers > 0 && g_debug_workers < w.workers) ? g_debug_workers : w.workers;
 }
 
 WorkspaceLayout append_layout(const rollattn_desc& d, int32_t total_q) {
@@ -152,10 +159,11 @@ int rollattn_debug_plan(const rollattn_desc* desc, const int32_t* ctx_lens_host,
   if (rc) return rc;
   if ((!ctx_lens_host && desc->batch > 0) || !per_out || !total_out || !n_segments) return ROLLATTN_EINVAL;
   const WorkspaceLayout w = decode_layout(*desc);
-  const HostPlan p = host_plan(ctx_lens_host, desc->batch, w.rows_per_b, w.workers);
+  const int32_t workers = plan_workers(w);
+  const HostPlan p = host_plan(ctx_lens_host, desc->batch, w.rows_per_b, workers);
   *per_out = p.per;
   *total_out = p.total;
-  *n_segments = expand_segments(p, desc->batch, w.rows_per_b, w.workers, segments_out, rollattn_plan_capacity(desc));
+  *n_segments = expand_segments(p, desc->batch, w.rows_per_b, workers, segments_out, rollattn_plan_capacity(desc));
   return ROLLATTN_OK;
 }
 
@@ -172,7 +180,7 @@ int rollattn_debug_read_plan(const rollattn_desc* desc, const void* workspace, i
   int32_t header[kPlanWords];
   e = hipMemcpy(header, base + w.header, sizeof(header), hipMemcpyDeviceToHost);
   if (e == hipSuccess)
-    e = hipMemcpy(starts_out, base + w.wstart, sizeof(int32_t) * 4 * (size_t)w.workers, hipMemcpyDeviceToHost);
+    e = hipMemcpy(starts_out, base + w.wstart, sizeof(int32_t) * 4 * (size_t)plan_workers(w), hipMemcpyDeviceToHost);
   if (e != hipSuccess) return fail_hip(e);
   *per_out = header[kPlanPer];
   *total_out = header[kPlanTotal];
@@ -210,7 +218,14 @@ int rollattn_debug_read_append_plan(const rollattn_desc* desc, const void* works
 
 int32_t rollattn_plan_workers(const rollattn_desc* desc) {
   if (check_desc(desc, false) != ROLLATTN_OK) return 0;
-  return decode_layout(*desc).workers;
+  return plan_workers(decode_layout(*desc));
+}
+
+int32_t rollattn_debug_set_decode_workers(int32_t workers) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  const int32_t before = g_debug_workers;
+  g_debug_workers = workers > 0 ? workers : 0;
+  return before;
 }
 
 // Shape limits of the decode path and of the append path beyond the descriptor checks; the entry points that
@@ -264,8 +279,9 @@ static int decode_impl(const rollattn_desc* desc, const void* q, const void* k_p
   a.q_lens = q_lens;
   a.q_offsets = q_offsets;
 
-  hipError_t e = launch_plan_decode(ctx_lens, q_lens, desc->batch, w.rows_per_b, w.workers, (int32_t*)(base + w.header),
-                                    (int32_t*)(base + w.prefix), (int32_t*)(base + w.wstart), s);
+  // (the launch has w.workers workers whatever the partition is cut for: the others get a record without blocks)
+  hipError_t e = launch_plan_decode(ctx_lens, q_lens, desc->batch, w.rows_per_b, plan_workers(w), w.workers,
+                                    (int32_t*)(base + w.header), (int32_t*)(base + w.prefix), (int32_t*)(base + w.wstart), s);
   if (e != hipSuccess) return fail_hip(e);
   const bool f32 = desc->q_dtype == ROLLATTN_F32;
   {

@@ -41,7 +41,7 @@ __device__ int block_exclusive_scan(int v, int* wave_tot /*[16]*/, int* total) {
 // With q_lens given (mixed step) only the trajectories with q_lens[b] == 1 take part; the others count as empty.
 __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ q_lens, int32_t batch, int32_t rows_per_b,
-    int32_t workers, int32_t* __restrict__ header, int32_t* __restrict__ prefix, int32_t* __restrict__ wstart) {
+    int32_t workers, int32_t slots, int32_t* __restrict__ header, int32_t* __restrict__ prefix, int32_t* __restrict__ wstart) {
   __shared__ int wave_tot[kPlanThreads / 64];
   __shared__ int prefix_s[kLdsPrefix + 1];
   const int tid = threadIdx.x;
@@ -77,10 +77,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(
   }
   __threadfence_block();
   __syncthreads();   // prefix[] written above is read below by other threads of this workgroup
-  for (int w = tid; w < workers; w += kPlanThreads) {
+  for (int w = tid; w < slots; w += kPlanThreads) {
     const long x = (long)w * per;
     int4 st = make_int4(-1, 0, 0, 0);
-    if (x < total) {
+    if (w < workers && x < total) {
       // largest b with rows_per_b * prefix[b] <= x (rows without blocks can never be the answer
       // because the next row then starts at the same position)
       const int* pf = in_lds ? prefix_s : prefix;
@@ -174,9 +174,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_append_kernel(
 }  // namespace
 
 hipError_t launch_plan_decode(const int32_t* ctx_lens, const int32_t* q_lens, int32_t batch, int32_t rows_per_b,
-                              int32_t workers, int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s) {
+                              int32_t workers, int32_t slots, int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s) {
   hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(kPlanThreads), 0, s, ctx_lens, q_lens, batch, rows_per_b, workers,
-                     header, prefix, wstart);
+                     slots, header, prefix, wstart);
   return hipGetLastError();
 }
 

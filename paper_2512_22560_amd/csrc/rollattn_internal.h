@@ -88,8 +88,9 @@ struct AppendArgs {
 };
 
 // Launchers (defined in the .hip files).  Each returns the hipError_t of its launch.
+// workers: how many the partition is cut for; slots >= workers: records written (those past `workers` say "no blocks")
 hipError_t launch_plan_decode(const int32_t* ctx_lens, const int32_t* q_lens, int32_t batch, int32_t rows_per_b,
-                              int32_t workers, int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s);
+                              int32_t workers, int32_t slots, int32_t* header, int32_t* prefix, int32_t* wstart, hipStream_t s);
 hipError_t launch_plan_append(const int32_t* q_lens, const int32_t* q_offsets, const int32_t* ctx_lens, int32_t batch,
                               int32_t tile_tokens, int32_t cap, bool skip_unit_chunks, int32_t* header, int32_t* tile_rec,
                               hipStream_t s);

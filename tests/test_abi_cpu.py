@@ -116,6 +116,12 @@ def test_descriptor_errors_are_reported_before_any_launch():
     assert lib.rollattn_workspace_bytes(ctypes.byref(_desc(head_dim=96)), 4) == 0
     assert lib.rollattn_workspace_bytes(ctypes.byref(_desc()), 4) > 0
     assert lib.rollattn_profile_read(None, 0) == 0
+    # the testing knob of the decode partition: fewer workers than the launch has, reported by rollattn_plan_workers
+    every = lib.rollattn_plan_workers(ctypes.byref(_desc()))
+    assert every > 7 and lib.rollattn_debug_set_decode_workers(7) == 0
+    assert lib.rollattn_plan_workers(ctypes.byref(_desc())) == 7
+    assert lib.rollattn_debug_set_decode_workers(10 ** 9) == 7 and lib.rollattn_plan_workers(ctypes.byref(_desc())) == every
+    assert lib.rollattn_debug_set_decode_workers(0) == 10 ** 9 and lib.rollattn_plan_workers(ctypes.byref(_desc())) == every
     assert lib.rollattn_profile_append_clock(None) == -1
     mhz = ctypes.c_double(-1.0)
     assert lib.rollattn_profile_append_clock(ctypes.byref(mhz)) == 0 and mhz.value == 0.0     # profiling never switched on

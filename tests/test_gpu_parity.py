@@ -16,6 +16,9 @@ from tests.helpers import oracle_args
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+# two results of the GPU path for the same inputs, computed with different splits: each within the parity bar of the oracle,
+# so at most twice that apart
+TOL_BETWEEN = {"f32": 2e-4, "bf16": 4e-2}
 
 
 def _wl(name, batch, hq, hkv, d, q_dtype, kv_dtype, ctx, qlen=("const", 1), seed=1, prefix=False, append_rows=None):
@@ -187,6 +190,36 @@ def test_device_plan_equals_host_twin_and_oracle_rule(seed, batch, hi, group):
     assert (per, total) == (h_per, h_total) == (o_per, o_total)
     assert np.array_equal(starts, o_starts)
     assert np.array_equal(h_segs, o_segs)
+
+
+@pytest.mark.parametrize("qd,kvd", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "fp8_e4m3")])
+def test_decode_does_not_depend_on_how_many_workers_cut_the_contexts(qd, kvd):
+    # one worker walks every row of the batch in turn; two and seven cut a few rows at odd places; a hundred cut most rows; the
+    # default cuts these short rows many times each: the same attention every time (and the plan is the oracle's rule for that number)
+    d = 64 if qd == "f32" else 128
+    b = W.build(_wl("cuts", 9, 8, 2, d, qd, kvd, ("loguniform", 1, 1500), seed=209), DEV)
+    ref = oracle_decode(b)
+    desc = B.make_desc(b.q, b.k_pages, b.page_table, sm_scale=b.workload.sm_scale, k_scale=b.k_scale, v_scale=b.v_scale)
+    rows_per_b = 2 * -(-4 // (4 if qd == "f32" else 16))
+    default = B.plan_workers(desc)
+    outs = {}
+    try:
+        for workers in (1, 2, 7, 100, 0):
+            B.set_decode_workers(workers)
+            assert B.plan_workers(desc) == (workers or default)
+            ws = B.alloc_workspace(desc, 9, DEV)
+            outs[workers] = gpu_decode(b, workspace=ws)
+            check(outs[workers], ref, qd, f"{workers} workers")
+            per, total, starts = B.read_plan(desc, ws)
+            o_per, o_total, o_starts, _ = O.split_plan(b.ctx_lens_host, rows_per_b, workers or default)
+            assert (per, total) == (o_per, o_total) and np.array_equal(starts, o_starts)
+            h_per, h_total, _ = B.debug_plan(desc, b.ctx_lens_host.astype(np.int32))
+            assert (h_per, h_total) == (o_per, o_total)
+    finally:
+        B.set_decode_workers(0)
+    tol = TOL_BETWEEN[qd]
+    for workers in (1, 2, 7, 100):
+        assert (outs[workers].float() - outs[0].float()).abs().max().item() <= tol
 
 
 @pytest.mark.parametrize("seed,batch,group,max_q,step,half", [
